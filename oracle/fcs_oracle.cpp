@@ -1,0 +1,434 @@
+// Plain CPU oracle for the slot-level model of one LLM-serving worker and the
+// flow-control admission rule (Section 2.1; Algorithm 2; Section 3.3).
+//
+// THIS FILE IS TEST INFRASTRUCTURE.  It is the slow, obviously-correct statement
+// of what a sample path is; only the tests, the smoke check and the benchmark's
+// CPU-baseline leg may call it.  It shares no code with the GPU engine: it has
+// its own Philox4x32-10, its own table inversion, its own queue mechanics, its
+// own counter layout.  Every quantity is recomputed from its definition (for
+// instance the KV usage is summed over the active set whenever it is needed).
+//
+// Model (per replica, slots t = 1..T; Q = waiting FIFO, P = active set in
+// activation order):
+//   1. arrivals       Section 2.1: n_t requests join the tail of Q.
+//   2. admission      FLOW  : Algorithm 2, move min(B_t, |Q|) head requests to P, no fit test.
+//                     GREEDY: the b -> infinity limit described after Theorem 2, with the
+//                             "initial memory l+1" fit test of Section 4.1: move the head
+//                             while usage-after-this-slot + l + 1 <= M.
+//   3. overflow       Algorithm 2 "if Overflow": the usage this slot is about to reach is
+//                     sum(l+j) + |P| (each active request may gain one token); while it
+//                     exceeds M evict the most recently activated request (LIFO rule of
+//                     Section 3.3); evicted requests lose all progress and go back to the
+//                     FRONT of Q (they keep their place by arrival order).
+//   4. process        token budget tau, chunk c (extension; with c >= l_max and tau = inf
+//                     it is the paper's "process all requests in P", where the activation
+//                     slot already yields token 1, cf. the expression for U_t in the proof
+//                     of Theorem 2): first the prefilling requests in activation order,
+//                     each advancing min(c, l-p, budget left), the slot that finishes the
+//                     prompt also yields the first token at no extra budget; then the
+//                     requests that were already decoding, in activation order, one token
+//                     each while budget lasts, the rest stall.
+//   5. measure        U_t = sum(l+j) over P (Section 2.1), |P_t|, |Q_t|.
+//   6. complete       j == o: completion slot c_i = t, footprint released at the end of
+//                     the same slot (Section 2.1); latency c_i - t_i + 1.
+//
+// Random draws: Philox4x32-10 (Salmon et al., SC'11), key = (seed lo, seed hi),
+// counter = (k, t, replica, purpose); purpose 0, k = 0: word0 -> n_t, word1 -> B_t;
+// purpose 1, k = index of the arrival within its slot: word0 -> class, word1 -> l,
+// word2 -> o.  Each word is inverted against a uint32 threshold table:
+// value = lo + #{i : u >= thr[i]}.
+//
+// parity unpinned: the budget order of step 4, the provisioned-usage reading of
+// "Overflow" in step 3 and the front-of-queue re-entry are this build's readings of
+// passages the paper leaves open; they are pinned only by hand-computed trajectories.
+#include <algorithm>
+#include <atomic>
+#include <cstdint>
+#include <cstring>
+#include <deque>
+#include <thread>
+#include <vector>
+
+extern "C" {
+
+struct fo_law {
+  int32_t lo;
+  int32_t n_thr;
+  const uint32_t* thr;
+};
+
+struct fo_config {
+  int32_t policy;  // 0 FLOW, 1 GREEDY
+  int32_t n_classes;
+  int64_t capacity;
+  int64_t token_budget;
+  int64_t prefill_chunk;
+  int32_t b_floor;
+  uint32_t b_frac_thr;
+  fo_law arrivals;
+  const uint32_t* class_thr;  // n_classes - 1
+  const fo_law* prompt;       // n_classes
+  const fo_law* decode;       // n_classes
+  int32_t trace_every;
+  int32_t hist_bins;
+  int32_t hist_shift;
+  int32_t reserved;
+  int64_t max_requests;
+  // forced inputs for hand-computed trajectories (n_forced < 0: draw from Philox)
+  int64_t n_forced;
+  const int32_t* forced_t;
+  const int32_t* forced_l;
+  const int32_t* forced_o;
+  int64_t n_forced_B;  // 0: draw B_t; else B_t = forced_B[min(t, n) - 1]
+  const int32_t* forced_B;
+};
+
+enum {
+  FO_COMPLETED = 0,
+  FO_ARRIVED,
+  FO_EVICTIONS,
+  FO_ACTIVATIONS,
+  FO_SUM_P,
+  FO_SUM_Q,
+  FO_SUM_U,
+  FO_OVERFLOW_STEPS,
+  FO_SUM_LATENCY,
+  FO_MAX_LATENCY,
+  FO_USEFUL_TOKENS,
+  FO_DECODE_TOKENS,
+  FO_PREFILL_TOKENS,
+  FO_STALLED,  // request-slots in which a decoding request got no token
+  FO_MAX_P,
+  FO_MAX_Q,
+  FO_MAX_U,
+  FO_FINAL_P,
+  FO_FINAL_Q,
+  FO_FINAL_U,
+  FO_DIGEST,
+  FO_N_COUNTERS
+};
+
+struct fo_outputs {
+  uint64_t* counters;        // [n_ids][FO_N_COUNTERS]
+  int32_t* trace_q;          // [n_ids][n_steps / trace_every] or null
+  int32_t* trace_u;          // same
+  uint32_t* hist;            // [n_ids][hist_bins] or null
+  int32_t* arrival_step;     // [n_ids][max_requests] or null (0 = no such request)
+  int32_t* completion_step;  // same (0 = not completed)
+  int32_t* first_activation; // same, oracle-only
+  int32_t* last_activation;  // same, oracle-only
+  int32_t* req_l;            // same, oracle-only
+  int32_t* req_o;            // same, oracle-only
+  int32_t* step_u;           // [n_ids][n_steps] or null, oracle-only
+  int32_t* step_p;
+  int32_t* step_q;
+  int32_t* step_n;           // arrivals drawn in each slot
+  int32_t* step_b;           // activation budget B_t of each slot (FLOW)
+};
+
+}  // extern "C"
+
+namespace {
+
+// ---- Philox4x32-10, written from the published definition ------------------
+inline void mulhilo(uint32_t a, uint32_t b, uint32_t& hi, uint32_t& lo) {
+  uint64_t p = static_cast<uint64_t>(a) * static_cast<uint64_t>(b);
+  hi = static_cast<uint32_t>(p >> 32);
+  lo = static_cast<uint32_t>(p);
+}
+
+void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+  uint32_t k0 = key[0], k1 = key[1];
+  for (int round = 0; round < 10; ++round) {
+    if (round > 0) {
+      k0 += 0x9E3779B9u;
+      k1 += 0xBB67AE85u;
+    }
+    uint32_t hi0, lo0, hi1, lo1;
+    mulhilo(0xD2511F53u, c0, hi0, lo0);
+    mulhilo(0xCD9E8D57u, c2, hi1, lo1);
+    uint32_t n0 = hi1 ^ c1 ^ k0;
+    uint32_t n1 = lo1;
+    uint32_t n2 = hi0 ^ c3 ^ k1;
+    uint32_t n3 = lo0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// value = lo + number of thresholds that are <= u
+int64_t invert(const fo_law& law, uint32_t u) {
+  int64_t n = 0;
+  for (int32_t i = 0; i < law.n_thr; ++i)
+    if (u >= law.thr[i]) ++n;
+  return law.lo + n;
+}
+
+// The same by bisection (thresholds are sorted); used on the long tables.
+int64_t invert_sorted(const fo_law& law, uint32_t u) {
+  const uint32_t* e = std::upper_bound(law.thr, law.thr + law.n_thr, u);
+  return law.lo + (e - law.thr);
+}
+
+struct Request {
+  int64_t id, l, o, t_arr;
+  int64_t p = 0;  // prompt tokens prefilled
+  int64_t j = 0;  // output tokens generated
+  bool was_active = false;
+  bool decoding_at_slot_start = false;
+};
+
+uint64_t fnv_step(uint64_t h, uint64_t word) { return (h ^ word) * 1099511628211ull; }
+
+int64_t usage(const std::vector<Request>& P) {  // Section 2.1: sum of (l_i + j_i)
+  int64_t u = 0;
+  for (const Request& r : P) u += r.l + r.j;
+  return u;
+}
+
+void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, int64_t slot,
+              const fo_outputs& out) {
+  const uint32_t key[2] = {static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32)};
+  const int64_t M = cfg.capacity;
+  std::deque<Request> Q;
+  std::vector<Request> P;
+  uint64_t* C = out.counters + slot * FO_N_COUNTERS;
+  std::memset(C, 0, sizeof(uint64_t) * FO_N_COUNTERS);
+  const int64_t n_trace = cfg.trace_every > 0 ? T / cfg.trace_every : 0;
+  int64_t next_id = 0;
+  int64_t forced_pos = 0;
+  auto rec = [&](int32_t* arr, int64_t id, int64_t v) {
+    if (arr && id < cfg.max_requests) arr[slot * cfg.max_requests + id] = static_cast<int32_t>(v);
+  };
+
+  for (int64_t t = 1; t <= T; ++t) {
+    // ---- 1. arrivals -------------------------------------------------------
+    uint32_t blk[4];
+    {
+      const uint32_t ctr[4] = {0u, static_cast<uint32_t>(t), static_cast<uint32_t>(replica), 0u};
+      philox4x32_10(ctr, key, blk);
+    }
+    int64_t n_t = 0;
+    if (cfg.n_forced >= 0) {
+      while (forced_pos < cfg.n_forced && cfg.forced_t[forced_pos] == t) {
+        Request r;
+        r.id = next_id++;
+        r.l = cfg.forced_l[forced_pos];
+        r.o = cfg.forced_o[forced_pos];
+        r.t_arr = t;
+        Q.push_back(r);
+        ++forced_pos;
+        ++n_t;
+      }
+    } else {
+      n_t = invert(cfg.arrivals, blk[0]);
+      for (int64_t k = 0; k < n_t; ++k) {
+        const uint32_t ctr[4] = {static_cast<uint32_t>(k), static_cast<uint32_t>(t),
+                                 static_cast<uint32_t>(replica), 1u};
+        uint32_t w[4];
+        philox4x32_10(ctr, key, w);
+        fo_law cls_law{0, cfg.n_classes - 1, cfg.class_thr};
+        int64_t cls = invert(cls_law, w[0]);
+        Request r;
+        r.id = next_id++;
+        r.l = invert_sorted(cfg.prompt[cls], w[1]);
+        r.o = invert_sorted(cfg.decode[cls], w[2]);
+        r.t_arr = t;
+        Q.push_back(r);
+      }
+    }
+    for (int64_t k = 0; k < n_t; ++k) {
+      const Request& r = Q[Q.size() - n_t + k];
+      rec(out.arrival_step, r.id, t);
+      rec(out.req_l, r.id, r.l);
+      rec(out.req_o, r.id, r.o);
+    }
+    C[FO_ARRIVED] += n_t;
+
+    // ---- 2. admission ------------------------------------------------------
+    int64_t B_t = 0;
+    auto activate_head = [&]() {
+      Request r = Q.front();
+      Q.pop_front();
+      r.p = 0;
+      r.j = 0;
+      if (!r.was_active) rec(out.first_activation, r.id, t);
+      rec(out.last_activation, r.id, t);
+      r.was_active = true;
+      P.push_back(r);
+      C[FO_ACTIVATIONS] += 1;
+    };
+    if (cfg.policy == 0) {
+      if (cfg.n_forced_B > 0)
+        B_t = cfg.forced_B[std::min<int64_t>(t, cfg.n_forced_B) - 1];
+      else
+        B_t = cfg.b_floor + (blk[1] < cfg.b_frac_thr ? 1 : 0);
+      int64_t activated = 0;
+      while (activated < B_t && !Q.empty()) {
+        activate_head();
+        ++activated;
+      }
+    } else {
+      while (!Q.empty()) {
+        int64_t provisioned = usage(P) + static_cast<int64_t>(P.size());
+        if (provisioned + Q.front().l + 1 > M) break;
+        activate_head();
+      }
+    }
+
+    // ---- 3. overflow: evict newest until the provisioned usage fits ---------
+    bool overflowed = false;
+    while (usage(P) + static_cast<int64_t>(P.size()) > M) {
+      Request r = P.back();
+      P.pop_back();
+      r.p = 0;
+      r.j = 0;
+      Q.push_front(r);
+      C[FO_EVICTIONS] += 1;
+      overflowed = true;
+    }
+    if (overflowed) C[FO_OVERFLOW_STEPS] += 1;
+
+    // ---- 4. process: prefill chunks first, then one token per decoding request
+    int64_t budget = cfg.token_budget;
+    for (Request& r : P) r.decoding_at_slot_start = (r.p == r.l);
+    for (Request& r : P) {
+      if (r.p == r.l) continue;
+      int64_t d = std::min(std::min(cfg.prefill_chunk, r.l - r.p), budget);
+      r.p += d;
+      budget -= d;
+      C[FO_PREFILL_TOKENS] += d;
+      if (r.p == r.l) {  // the chunk that ends the prompt also yields token 1
+        r.j = 1;
+        C[FO_DECODE_TOKENS] += 1;
+      }
+    }
+    for (Request& r : P) {
+      if (!r.decoding_at_slot_start) continue;
+      if (budget > 0) {
+        r.j += 1;
+        budget -= 1;
+        C[FO_DECODE_TOKENS] += 1;
+      } else {
+        C[FO_STALLED] += 1;
+      }
+    }
+
+    // ---- 5. measure ----------------------------------------------------------
+    const int64_t U_t = usage(P);
+    const int64_t P_t = static_cast<int64_t>(P.size());
+    const int64_t Q_t = static_cast<int64_t>(Q.size());
+    C[FO_SUM_U] += U_t;
+    C[FO_SUM_P] += P_t;
+    C[FO_SUM_Q] += Q_t;
+    C[FO_MAX_U] = std::max<uint64_t>(C[FO_MAX_U], U_t);
+    C[FO_MAX_P] = std::max<uint64_t>(C[FO_MAX_P], P_t);
+    C[FO_MAX_Q] = std::max<uint64_t>(C[FO_MAX_Q], Q_t);
+    if (cfg.trace_every > 0 && t % cfg.trace_every == 0) {
+      int64_t idx = t / cfg.trace_every - 1;
+      if (out.trace_q) out.trace_q[slot * n_trace + idx] = static_cast<int32_t>(Q_t);
+      if (out.trace_u) out.trace_u[slot * n_trace + idx] = static_cast<int32_t>(U_t);
+    }
+    if (out.step_u) out.step_u[slot * T + (t - 1)] = static_cast<int32_t>(U_t);
+    if (out.step_p) out.step_p[slot * T + (t - 1)] = static_cast<int32_t>(P_t);
+    if (out.step_q) out.step_q[slot * T + (t - 1)] = static_cast<int32_t>(Q_t);
+    if (out.step_n) out.step_n[slot * T + (t - 1)] = static_cast<int32_t>(n_t);
+    if (out.step_b) out.step_b[slot * T + (t - 1)] = static_cast<int32_t>(B_t);
+
+    // ---- 6. complete ---------------------------------------------------------
+    std::vector<Request> keep;
+    keep.reserve(P.size());
+    for (const Request& r : P) {
+      if (r.j == r.o) {
+        int64_t latency = t - r.t_arr + 1;
+        C[FO_COMPLETED] += 1;
+        C[FO_SUM_LATENCY] += latency;
+        C[FO_MAX_LATENCY] = std::max<uint64_t>(C[FO_MAX_LATENCY], latency);
+        C[FO_USEFUL_TOKENS] += r.o;
+        rec(out.completion_step, r.id, t);
+        if (out.hist && cfg.hist_bins > 0) {
+          int64_t b = std::min<int64_t>(latency >> cfg.hist_shift, cfg.hist_bins - 1);
+          out.hist[slot * cfg.hist_bins + b] += 1;
+        }
+      } else {
+        keep.push_back(r);
+      }
+    }
+    P.swap(keep);
+  }
+
+  C[FO_FINAL_P] = P.size();
+  C[FO_FINAL_Q] = Q.size();
+  C[FO_FINAL_U] = usage(P);
+  // digest of the final state: FNV-1a over 64-bit words
+  uint64_t h = 14695981039346656037ull;
+  h = fnv_step(h, P.size());
+  for (const Request& r : P) {
+    h = fnv_step(h, r.id);
+    h = fnv_step(h, r.j);
+    h = fnv_step(h, r.p);
+  }
+  uint64_t returned = 0;
+  for (const Request& r : Q) returned += r.was_active ? 1 : 0;
+  h = fnv_step(h, returned);
+  for (const Request& r : Q)
+    if (r.was_active) h = fnv_step(h, r.id);
+  h = fnv_step(h, Q.size() - returned);
+  C[FO_DIGEST] = h;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fo_n_counters() { return FO_N_COUNTERS; }
+
+const char* fo_counter_name(int i) {
+  static const char* names[FO_N_COUNTERS] = {
+      "completed", "arrived", "evictions", "activations", "sum_p", "sum_q", "sum_u",
+      "overflow_steps", "sum_latency", "max_latency", "useful_tokens", "decode_tokens",
+      "prefill_tokens", "stalled", "max_p", "max_q", "max_u", "final_p", "final_q",
+      "final_u", "digest"};
+  return (i >= 0 && i < FO_N_COUNTERS) ? names[i] : nullptr;
+}
+
+void fo_philox(const uint32_t* ctr, const uint32_t* key, uint32_t* out) {
+  philox4x32_10(ctr, key, out);
+}
+
+// Inverts n words against one law with both search routines; returns -1 if they differ.
+int fo_invert(const fo_law* law, const uint32_t* u, int64_t n, int64_t* out) {
+  for (int64_t i = 0; i < n; ++i) {
+    out[i] = invert(*law, u[i]);
+    if (out[i] != invert_sorted(*law, u[i])) return -1;
+  }
+  return 0;
+}
+
+// Simulates the listed replicas (the Philox replica index is replica_ids[i]);
+// output row i belongs to replica_ids[i].  Returns 0, or -1 on bad arguments.
+int fo_run(const fo_config* cfg, int64_t n_ids, const int64_t* replica_ids, int64_t n_steps,
+           uint64_t seed, int32_t n_threads, const fo_outputs* out) {
+  if (!cfg || !out || !out->counters || n_ids < 0 || n_steps < 0) return -1;
+  if (cfg->policy != 0 && cfg->policy != 1) return -1;
+  if (cfg->capacity < 1 || cfg->token_budget < 1 || cfg->prefill_chunk < 1) return -1;
+  if (n_threads < 1) n_threads = 1;
+  if (out->hist && cfg->hist_bins > 0)
+    std::memset(out->hist, 0, sizeof(uint32_t) * n_ids * cfg->hist_bins);
+  std::atomic<int64_t> next{0};
+  auto worker = [&]() {
+    for (;;) {
+      int64_t i = next.fetch_add(1);
+      if (i >= n_ids) break;
+      simulate(*cfg, replica_ids[i], n_steps, seed, i, *out);
+    }
+  };
+  std::vector<std::thread> pool;
+  for (int32_t k = 1; k < n_threads; ++k) pool.emplace_back(worker);
+  worker();
+  for (auto& th : pool) th.join();
+  return 0;
+}
+
+}  // extern "C"

@@ -1,0 +1,197 @@
+"""Seeded synthetic workloads: the five benchmark configurations and small variants.
+
+A :class:`Workload` is a complete, simulator-agnostic description of one run:
+capacity M, token budget, prefill chunk, the length mixture nu, a list of
+arrival-count laws, and a list of *cells* (policy, arrival law, activation
+budget b) that all share the same random streams.  Each cell is simulated for
+``n_replicas`` independent sample paths of ``n_steps`` slots.
+
+The arrival rates of most configurations are stated as multiples of the paper's
+necessary-condition bound (Proposition 2, eq. 3).  That bound is part of the
+method, so it is *not* computed here: the caller passes ``stability_bound``, a
+function ``(Mixture, capacity) -> float``.
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+from typing import Callable, Sequence
+
+import numpy as np
+
+from . import laws
+from .laws import Law, Mixture, RequestClass
+
+FLOW = 0     # Algorithm 2: rate-limited activation, LIFO eviction on overflow
+GREEDY = 1   # b -> infinity limit with a memory fit test: admit while it fits, evict newest
+
+
+@dataclasses.dataclass(frozen=True)
+class Cell:
+    policy: int
+    arrival: int          # index into Workload.arrival_laws
+    b_floor: int          # B_t = b_floor + [u < b_frac_thr]   (ignored by GREEDY)
+    b_frac_thr: int
+    label: str = ""
+
+
+@dataclasses.dataclass(frozen=True)
+class Workload:
+    name: str
+    capacity: int
+    token_budget: int
+    prefill_chunk: int
+    mixture: Mixture
+    arrival_laws: tuple
+    cells: tuple
+    n_replicas: int
+    n_steps: int
+    seed: int
+    trace_every: int = 0
+    hist_bins: int = 0
+    hist_shift: int = 0
+    max_requests: int = 0      # per-path capacity of the per-request record arrays (0 = off)
+    notes: str = ""
+
+    def scaled(self, n_replicas: int | None = None, n_steps: int | None = None, **kw) -> "Workload":
+        d = {}
+        if n_replicas is not None:
+            d["n_replicas"] = int(n_replicas)
+        if n_steps is not None:
+            d["n_steps"] = int(n_steps)
+        d.update(kw)
+        return dataclasses.replace(self, **d)
+
+    @property
+    def n_paths(self) -> int:
+        return len(self.cells) * self.n_replicas
+
+
+def split_b(b: float):
+    """b -> (floor(b), threshold of the fractional part): B_t = floor + Bernoulli(frac)."""
+    fl = int(math.floor(b))
+    return fl, laws.frac_threshold(b - fl)
+
+
+def default_b(lam: float, lam_star: float) -> float:
+    """Midpoint between the arrival rate and the bound while below it, the bound itself otherwise."""
+    return 0.5 * (lam + lam_star) if lam < lam_star else lam_star
+
+
+def flow_cell(arrival: int, b: float, label: str = "") -> Cell:
+    fl, th = split_b(b)
+    return Cell(FLOW, arrival, fl, th, label or f"flow(b={b:.6g})")
+
+
+def greedy_cell(arrival: int, label: str = "greedy") -> Cell:
+    return Cell(GREEDY, arrival, 0, 0, label)
+
+
+Bound = Callable[[Mixture, int], float]
+
+
+def config0(bound: Bound) -> Workload:
+    M = 16384
+    mix = laws.single(laws.uniform_int(16, 256), laws.geometric(128.0, cap=1024))
+    lam = 0.05
+    ls = bound(mix, M)
+    return Workload(
+        name="cfg0-tiny-flow", capacity=M, token_budget=512, prefill_chunk=512, mixture=mix,
+        arrival_laws=(laws.bernoulli_counts(lam),),
+        cells=(flow_cell(0, default_b(lam, ls)),),
+        n_replicas=64, n_steps=10_000, seed=1, max_requests=1024,
+        notes=f"lambda={lam}, bound={ls:.6g}")
+
+
+def config1(bound: Bound) -> Workload:
+    M = 262144
+    mix = laws.single(laws.lognormal(6.0, 0.8, 8, 8192), laws.lognormal(5.5, 1.0, 1, 16384))
+    ls = bound(mix, M)
+    lam = 0.9 * ls
+    return Workload(
+        name="cfg1-flow-vs-greedy", capacity=M, token_budget=2048, prefill_chunk=512, mixture=mix,
+        arrival_laws=(laws.poisson_counts(lam),),
+        cells=(flow_cell(0, default_b(lam, ls)), greedy_cell(0)),
+        n_replicas=1024, n_steps=100_000, seed=2, hist_bins=0,
+        notes=f"lambda={lam:.6g} (0.9 x bound {ls:.6g})")
+
+
+def config2(bound: Bound) -> Workload:
+    M = 524288
+    mix = laws.single(laws.uniform_int(64, 4096), laws.pareto(1.5, 32.0, 32768))
+    ls = bound(mix, M)
+    factors = (0.8, 0.95, 1.05)
+    arr = tuple(laws.poisson_counts(f * ls) for f in factors)
+    cells = tuple(flow_cell(i, default_b(f * ls, ls), f"flow(lambda={f}xbound)") for i, f in enumerate(factors))
+    return Workload(
+        name="cfg2-heavy-tail", capacity=M, token_budget=4096, prefill_chunk=1024, mixture=mix,
+        arrival_laws=arr, cells=cells, n_replicas=4096, n_steps=200_000, seed=3, trace_every=1000,
+        notes=f"bound={ls:.6g}")
+
+
+def config3(bound: Bound, n_lambda: int = 64, n_b: int = 32) -> Workload:
+    M = 131072
+    mix = laws.single(laws.geometric(512.0), laws.geometric(256.0))
+    ls = bound(mix, M)
+    lam_f = np.linspace(0.5, 1.1, n_lambda)
+    b_f = np.linspace(0.5, 1.5, n_b)
+    arr = tuple(laws.poisson_counts(float(f) * ls) for f in lam_f)
+    cells = []
+    for i, f in enumerate(lam_f):
+        for g in b_f:
+            cells.append(flow_cell(i, float(g) * ls, f"flow(lambda={f:.4f}x,b={g:.4f}x)"))
+    return Workload(
+        name="cfg3-grid", capacity=M, token_budget=1024, prefill_chunk=256, mixture=mix,
+        arrival_laws=arr, cells=tuple(cells), n_replicas=128, n_steps=50_000, seed=4,
+        hist_bins=4096, hist_shift=1, notes=f"bound={ls:.6g}")
+
+
+def config4(bound: Bound) -> Workload:
+    M = 2097152
+    short = RequestClass(0.7, laws.lognormal(5.0, 0.5, 1, 32768), laws.geometric(64.0))
+    long_ = RequestClass(0.3, laws.lognormal(8.0, 0.5, 1, 32768), laws.lognormal(7.0, 1.0, 1, 65536))
+    mix = Mixture((short, long_))
+    ls = bound(mix, M)
+    lam = 0.95 * ls
+    return Workload(
+        name="cfg4-large-memory", capacity=M, token_budget=8192, prefill_chunk=2048, mixture=mix,
+        arrival_laws=(laws.poisson_counts(lam),),
+        cells=(flow_cell(0, default_b(lam, ls)),),
+        n_replicas=512, n_steps=1_000_000, seed=5,
+        notes=f"lambda={lam:.6g} (0.95 x bound {ls:.6g})")
+
+
+CONFIGS = (config0, config1, config2, config3, config4)
+
+
+def make(index: int, bound: Bound) -> Workload:
+    return CONFIGS[index](bound)
+
+
+def three_class(lam_per_class: float, capacity: int = 16492, b: float = 12.0,
+                n_replicas: int = 8, n_steps: int = 2000, seed: int = 7) -> Workload:
+    """The paper's synthetic study shape (Section 4.1): l=10, o in {20,40,60}, equal Poisson rates."""
+    cls = tuple(RequestClass(1.0, laws.point(10), laws.point(o)) for o in (20, 40, 60))
+    mix = Mixture(cls)
+    return Workload(
+        name="three-class", capacity=capacity, token_budget=1 << 20, prefill_chunk=1 << 20, mixture=mix,
+        arrival_laws=(laws.poisson_counts(3.0 * lam_per_class),),
+        cells=(flow_cell(0, b), greedy_cell(0)),
+        n_replicas=n_replicas, n_steps=n_steps, seed=seed, max_requests=1 << 16)
+
+
+def toy(capacity: int = 600, token_budget: int = 96, prefill_chunk: int = 32, lam: float = 0.6,
+        b: float = 0.8, l_range=(4, 60), o_mean: float = 12.0, o_cap: int = 80,
+        n_replicas: int = 16, n_steps: int = 400, seed: int = 11,
+        policies: Sequence[int] = (FLOW, GREEDY), **kw) -> Workload:
+    """A small, eviction-heavy workload for exhaustive checks."""
+    mix = laws.single(laws.uniform_int(*l_range), laws.geometric(o_mean, cap=o_cap))
+    cells = []
+    for p in policies:
+        cells.append(flow_cell(0, b) if p == FLOW else greedy_cell(0))
+    return Workload(
+        name="toy", capacity=capacity, token_budget=token_budget, prefill_chunk=prefill_chunk, mixture=mix,
+        arrival_laws=(laws.poisson_counts(lam),), cells=tuple(cells), n_replicas=n_replicas,
+        n_steps=n_steps, seed=seed, trace_every=kw.pop("trace_every", 10),
+        hist_bins=kw.pop("hist_bins", 256), hist_shift=kw.pop("hist_shift", 0),
+        max_requests=kw.pop("max_requests", 2048), **kw)
