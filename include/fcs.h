@@ -1,0 +1,222 @@
+/*
+ * fcs.h - C ABI of the flow-controlled-scheduling sample-path engine (gfx950).
+ *
+ * The engine evaluates, as many independent sample paths, the slotted model of
+ * one LLM-serving worker with a KV-cache budget M (Section 2.1 of the paper)
+ * under the flow-control admission rule with unknown output length
+ * (Algorithm 2, Section 3.3) and under its greedy limit (remark after
+ * Theorem 2; fit test "initial memory l+1" of Section 4.1), extended by a
+ * per-slot token budget and chunked prefill (Section 1 describes both as
+ * current practice; the paper's pure model is recovered with chunk >= l_max
+ * and an unlimited budget).
+ *
+ * One slot of one path, in this order:
+ *   1. n_t requests arrive and join the tail of the waiting queue Q.
+ *   2. admission.  FLOW: the first min(B_t, |Q|) requests of Q join the active
+ *      set P, B_t = b_floor + [u < b_frac_thr].  GREEDY: the head of Q joins
+ *      while (sum_P (l+j)) + |P| + l_head + 1 <= M.
+ *   3. overflow.  While (sum_P (l+j)) + |P| > M the most recently activated
+ *      request is evicted: it loses its progress and returns to the FRONT of Q.
+ *   4. processing with token budget tau and chunk c.  Prefilling requests, in
+ *      activation order, advance min(c, l-p, budget left); the slot in which
+ *      the prompt ends also yields output token 1 at no extra budget.  Then the
+ *      requests that were already decoding, in activation order, gain one token
+ *      each while budget lasts; the others stall.
+ *   5. U_t = sum_P (l+j), |P_t| and |Q_t| are measured.
+ *   6. requests with j == o complete: completion slot t, latency t - t_arr + 1,
+ *      footprint released at the end of the slot.
+ *
+ * Randomness.  Philox4x32-10 with key (seed & 0xffffffff, seed >> 32) and
+ * counter (k, t, replica, purpose).  purpose 0, k 0: word 0 -> n_t, word 1 ->
+ * B_t.  purpose 1, k = index of the arrival within slot t: word 0 -> class,
+ * word 1 -> l, word 2 -> o.  A word u is inverted against a law's threshold
+ * table: value = lo + #{ i : u >= thr[i] }.  All cells of one engine see the
+ * same words (the policy and the cell are not part of the counter), so cells
+ * are compared on identical arrival streams.
+ *
+ * Memory and ownership.  The library allocates no device memory.  The caller
+ * owns one device workspace (size from fcs_workspace_bytes) and the device
+ * output arrays of fcs_outputs, and passes raw device pointers; "stream" is a
+ * hipStream_t passed as void*.  All fcs_law/fcs_cell/fcs_params pointers are
+ * HOST pointers and are copied by fcs_create; they may be freed afterwards.
+ *
+ * Errors.  Every call returns FCS_OK (0) or a negative code; nothing throws or
+ * aborts across this boundary.  The library needs a HIP device: there is no
+ * CPU fallback, and calls that need the GPU return FCS_EDEVICE without one.
+ */
+#ifndef FCS_H_
+#define FCS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fcs_engine* fcs_handle;
+
+enum {
+  FCS_OK = 0,
+  FCS_EINVAL = -1,    /* bad argument or parameter combination                    */
+  FCS_ENOMEM = -2,    /* workspace too small / host allocation failed             */
+  FCS_ESTATE = -3,    /* call out of order (run before bind, stats before run)    */
+  FCS_EOVERFLOW = -4, /* a path outgrew max_active or produced >= 2^31 arrivals   */
+  FCS_EDEVICE = -5    /* HIP error or no device                                   */
+};
+
+enum { FCS_POLICY_FLOW = 0, FCS_POLICY_GREEDY = 1 };
+
+/* Integer law on {lo, ..., lo + n_thr}; thr non-decreasing (host pointer). */
+typedef struct fcs_law {
+  int32_t lo;
+  int32_t n_thr;
+  const uint32_t* thr;
+} fcs_law;
+
+/* One policy setting evaluated on the shared random streams. */
+typedef struct fcs_cell {
+  int32_t policy;      /* FCS_POLICY_*                                             */
+  int32_t arrival;     /* index into fcs_params.arrival                            */
+  int32_t b_floor;     /* FLOW: B_t = b_floor + [u < b_frac_thr]  (Theorem 2: any  */
+  uint32_t b_frac_thr; /*   bounded i.i.d. integer budget with mean b)             */
+} fcs_cell;
+
+typedef struct fcs_params {
+  int32_t capacity;       /* M, tokens, 1 .. 2^30                                  */
+  int32_t token_budget;   /* tau per slot, 1 .. 2^30                               */
+  int32_t prefill_chunk;  /* c, 1 .. 2^30                                          */
+  int32_t n_classes;      /* classes of the length mixture nu, 1 .. 16             */
+  const uint32_t* class_thr; /* n_classes - 1 cumulative class thresholds          */
+  const fcs_law* prompt;  /* per class: law of l, lo >= 1                          */
+  const fcs_law* decode;  /* per class: law of o, lo >= 1; max l + max o <= M      */
+  int32_t n_arrival_laws;
+  const fcs_law* arrival; /* laws of n_t (lo = 0, at most 63 thresholds)           */
+  int32_t n_cells;
+  const fcs_cell* cells;
+  int32_t trace_every;    /* > 0: record (|Q_t|, U_t) at t = k, 2k, ...            */
+  int32_t hist_bins;      /* > 0: latency histogram, bucket = min(lat >> shift, bins-1) */
+  int32_t hist_shift;
+  int32_t max_requests;   /* > 0: per-path length of arrival_step/completion_step  */
+  int32_t max_active;     /* per-path capacity of the active set; 0 = default      */
+  int32_t lds_slots;      /* active-set slots kept in LDS per path; 0 = automatic  */
+} fcs_params;
+
+/* Per-path counters, uint64 each, FCS_N_COUNTERS per path. */
+enum {
+  FCS_C_ARRIVED = 0,     /* requests arrived in slots 1..T                          */
+  FCS_C_ACTIVATIONS,     /* activations, re-activations after eviction included     */
+  FCS_C_COMPLETED,
+  FCS_C_EVICTIONS,
+  FCS_C_OVERFLOW_STEPS,  /* slots with at least one eviction                        */
+  FCS_C_SUM_U,           /* sum_t U_t                                               */
+  FCS_C_SUM_P,           /* sum_t |P_t| : the request-steps of the path             */
+  FCS_C_SUM_Q,           /* sum_t |Q_t|                                             */
+  FCS_C_DECODE_TOKENS,   /* output tokens generated, discarded ones included        */
+  FCS_C_PREFILL_TOKENS,  /* prompt tokens processed, discarded ones included        */
+  FCS_C_USEFUL_TOKENS,   /* sum of o over completed requests                        */
+  FCS_C_STALLED,         /* request-slots in which a decoding request got no token  */
+  FCS_C_SUM_LATENCY,     /* sum of (completion - arrival + 1) over completed        */
+  FCS_C_MAX_LATENCY,
+  FCS_C_MAX_U,
+  FCS_C_MAX_P,
+  FCS_C_MAX_Q,
+  FCS_C_FINAL_U,
+  FCS_C_FINAL_P,
+  FCS_C_FINAL_Q,
+  FCS_C_DIGEST,          /* FNV-1a (64-bit words) of the final state, see below     */
+  FCS_C_ERROR,           /* 0, or -code of the error that stopped the path          */
+  FCS_C_ERROR_STEP,      /* slot at which it stopped                                */
+  FCS_C_RESERVED,
+  FCS_N_COUNTERS
+};
+/* Digest: h = 14695981039346656037; for each word x: h = (h ^ x) * 1099511628211.
+ * Words: |P|; for each active request in activation order: id, j, p; the number
+ * of waiting requests that were active before; their ids in queue order; the
+ * number of waiting requests never activated.  ids number a path's arrivals
+ * 0,1,2,... in order of (slot, index within slot). */
+
+/* Device output arrays (caller-owned).  counters is required; the others may be
+ * NULL, and must be non-NULL only if the matching parameter is > 0 and wanted. */
+typedef struct fcs_outputs {
+  uint64_t* counters;        /* [n_paths][FCS_N_COUNTERS]                           */
+  int32_t* trace_q;          /* [n_paths][n_steps / trace_every]                    */
+  int32_t* trace_u;          /* same shape                                          */
+  uint32_t* hist;            /* [n_paths][hist_bins]                                */
+  int32_t* arrival_step;     /* [n_paths][max_requests], 0 = no such request        */
+  int32_t* completion_step;  /* [n_paths][max_requests], 0 = not completed          */
+} fcs_outputs;
+/* path = cell * n_replicas + replica. */
+
+typedef struct fcs_summary {
+  int64_t n_paths;
+  int64_t n_steps;
+  uint64_t request_steps;   /* sum of FCS_C_SUM_P                                   */
+  uint64_t arrived;
+  uint64_t completed;
+  uint64_t evictions;
+  uint64_t overflow_steps;
+  double mean_latency;      /* slots, over completed requests (Section 2.2)         */
+  double kv_utilisation;    /* sum_t U_t / (T * M), averaged over paths             */
+  double token_throughput;  /* useful output tokens per slot per path (Section 2.2) */
+  double prompt_throughput; /* completed requests per slot per path                 */
+  double mean_queue;        /* time-average |Q_t|                                   */
+  double mean_active;       /* time-average |P_t|                                   */
+  int64_t first_error_path; /* -1 if no path stopped with an error                  */
+  int32_t error_code;
+  int32_t reserved;
+} fcs_summary;
+
+/* Validates and copies the parameters.  FCS_EINVAL on any violated range above,
+ * a decreasing threshold table, or max(l) + max(o) > M (Section 2.1 requires
+ * U_t <= M; a request that cannot fit alone would be evicted forever). */
+int fcs_create(const fcs_params* params, fcs_handle* out);
+
+/* Bytes of device workspace needed to run n_replicas paths per cell. */
+int fcs_workspace_bytes(fcs_handle h, int64_t n_replicas, size_t* bytes);
+
+/* Uploads the tables into the workspace (asynchronously on stream) and records
+ * the workspace and output pointers.  workspace must be 256-byte aligned.
+ * FCS_ENOMEM if bytes is too small for n_replicas. */
+int fcs_bind(fcs_handle h, void* dev_workspace, size_t bytes, int64_t n_replicas,
+             const fcs_outputs* dev_out, void* stream);
+
+/* Simulates n_replicas sample paths per cell for slots 1..n_steps (Algorithm 2's
+ * loop over t), replica r of every cell using Philox replica index
+ * replica_base + r.  Asynchronous on stream; one workgroup of one wavefront per
+ * path.  n_replicas must not exceed the bound value; 1 <= n_steps < 2^30. */
+int fcs_run(fcs_handle h, int64_t n_replicas, int64_t n_steps, uint64_t seed, void* stream);
+
+/* Same with an explicit first replica index (sharding a sweep over devices). */
+int fcs_run_from(fcs_handle h, int64_t replica_base, int64_t n_replicas, int64_t n_steps,
+                 uint64_t seed, void* stream);
+
+/* Waits for the last run, copies the per-path counters to host_counters
+ * ([n_paths][FCS_N_COUNTERS], may be NULL) and fills the summary of one cell
+ * (cell >= 0) or of all paths (cell = -1).  Returns FCS_EOVERFLOW if a path
+ * stopped with an error (the summary still describes what was simulated). */
+int fcs_stats(fcs_handle h, int32_t cell, uint64_t* host_counters, fcs_summary* summary);
+
+/* Nearest-rank percentile num/den of the request latency of every path, from
+ * the device histogram of the last run (Section 4: average and tail latency):
+ * value[p] = (bucket of the ceil(q*n)-th smallest latency) << hist_shift,
+ * saturated[p] = 1 if that is the last bucket.  Host output arrays of n_paths. */
+int fcs_percentile(fcs_handle h, int64_t num, int64_t den, int32_t* value, uint8_t* saturated);
+
+/* lambda* = M / E[l o + (o + o^2)/2] for the parameter's mixture (Proposition 2,
+ * eq. 3), l and o independent within a class.  Host only. */
+int fcs_stability_bound(const fcs_params* params, double* lambda_star);
+
+/* Launch geometry chosen by fcs_bind: LDS slots per path, LDS bytes per workgroup,
+ * spill slots per path. */
+int fcs_geometry(fcs_handle h, int32_t* lds_slots, int32_t* lds_bytes, int32_t* spill_slots);
+
+void fcs_destroy(fcs_handle h);
+const char* fcs_strerror(int code);
+int fcs_n_counters(void);
+const char* fcs_counter_name(int index);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FCS_H_ */

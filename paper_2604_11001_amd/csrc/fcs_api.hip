@@ -1,0 +1,420 @@
+// Host side of libfcs: parameter validation, table blob, workspace layout, launches,
+// read-back and derived statistics.  See include/fcs.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "fcs_internal.h"
+
+using namespace fcs;
+
+struct fcs_engine {
+  // parameters (owned copies)
+  int32_t M = 0, tau = 0, chunk = 0, n_classes = 0, n_arrival_laws = 0, n_cells = 0;
+  int32_t trace_every = 0, hist_bins = 0, hist_shift = 0, max_requests = 0;
+  int32_t max_active = 0, lds_slots_param = 0;
+  int32_t l_min = 1;
+  std::vector<DCell> cells;
+  std::vector<uint32_t> blob;  // DLaw[], DCell[], class thresholds, thresholds, guides
+  uint32_t laws_off = 0, cells_off = 0, class_off = 0;
+  // binding
+  bool bound = false;
+  void* workspace = nullptr;
+  size_t workspace_bytes = 0;
+  int64_t bound_replicas = 0;
+  fcs_outputs out{};
+  int32_t lcap = 0, hcap = 0, hscap = 0;
+  int64_t spill_stride = 0;
+  size_t blob_bytes_padded = 0;
+  // last run
+  bool ran = false;
+  int64_t run_replicas = 0, run_steps = 0;
+  void* run_stream = nullptr;
+};
+
+namespace {
+
+constexpr int32_t kLimit = 1 << 30;
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+bool law_ok(const fcs_law& L, int32_t min_lo, int32_t max_thr) {
+  if (L.lo < min_lo || L.n_thr < 0 || L.n_thr > max_thr) return false;
+  if (L.n_thr > 0 && L.thr == nullptr) return false;
+  if (static_cast<int64_t>(L.lo) + L.n_thr > kLimit) return false;
+  for (int32_t i = 1; i < L.n_thr; ++i)
+    if (L.thr[i] < L.thr[i - 1]) return false;
+  return true;
+}
+
+bool params_ok(const fcs_params* p) {
+  if (!p) return false;
+  if (p->capacity < 1 || p->capacity > kLimit) return false;
+  if (p->token_budget < 1 || p->token_budget > kLimit) return false;
+  if (p->prefill_chunk < 1 || p->prefill_chunk > kLimit) return false;
+  if (p->n_classes < 1 || p->n_classes > kMaxClasses || !p->prompt || !p->decode) return false;
+  if (p->n_classes > 1 && !p->class_thr) return false;
+  for (int32_t c = 0; c + 2 < p->n_classes; ++c)
+    if (p->class_thr[c + 1] < p->class_thr[c]) return false;
+  int64_t l_max = 0, o_max = 0;
+  for (int32_t c = 0; c < p->n_classes; ++c) {
+    if (!law_ok(p->prompt[c], 1, 1 << 24) || !law_ok(p->decode[c], 1, 1 << 24)) return false;
+    l_max = std::max<int64_t>(l_max, static_cast<int64_t>(p->prompt[c].lo) + p->prompt[c].n_thr);
+    o_max = std::max<int64_t>(o_max, static_cast<int64_t>(p->decode[c].lo) + p->decode[c].n_thr);
+  }
+  if (l_max + o_max > p->capacity) return false;
+  if (p->n_arrival_laws < 1 || !p->arrival) return false;
+  for (int32_t a = 0; a < p->n_arrival_laws; ++a)
+    if (!law_ok(p->arrival[a], 0, kMaxCountThr) || p->arrival[a].lo != 0) return false;
+  if (p->n_cells < 1 || !p->cells) return false;
+  for (int32_t i = 0; i < p->n_cells; ++i) {
+    const fcs_cell& c = p->cells[i];
+    if (c.policy != FCS_POLICY_FLOW && c.policy != FCS_POLICY_GREEDY) return false;
+    if (c.arrival < 0 || c.arrival >= p->n_arrival_laws) return false;
+    if (c.b_floor < 0 || c.b_floor > 30000) return false;
+  }
+  if (p->trace_every < 0 || p->hist_bins < 0 || p->hist_bins > (1 << 24)) return false;
+  if (p->hist_shift < 0 || p->hist_shift > 30 || p->max_requests < 0) return false;
+  if (p->max_active < 0 || p->max_active > (1 << 24)) return false;
+  if (p->lds_slots != 0 &&
+      (p->lds_slots < kLdsBlock || p->lds_slots > 4096 || p->lds_slots % kLdsBlock != 0))
+    return false;
+  return true;
+}
+
+void append_law(std::vector<uint32_t>& blob, std::vector<DLaw>& laws, const fcs_law& L, bool guide) {
+  DLaw d;
+  d.lo = L.lo;
+  d.n = L.n_thr;
+  d.off = static_cast<uint32_t>(blob.size());
+  blob.insert(blob.end(), L.thr, L.thr + L.n_thr);
+  d.goff = 0;
+  if (guide) {
+    d.goff = static_cast<uint32_t>(blob.size());
+    for (uint32_t b = 0; b <= 256; ++b) {
+      // guide[b] = number of thresholds strictly below b << 24 (all of them for b = 256)
+      uint32_t cnt;
+      if (b == 256) cnt = static_cast<uint32_t>(L.n_thr);
+      else cnt = static_cast<uint32_t>(std::lower_bound(L.thr, L.thr + L.n_thr, b << 24) - L.thr);
+      blob.push_back(cnt);
+    }
+  }
+  laws.push_back(d);
+}
+
+// E[X^k] of a threshold-table law, k = 1, 2
+void law_moments(const fcs_law& L, double& m1, double& m2) {
+  const double two32 = 4294967296.0;
+  double prev = 0.0;
+  m1 = m2 = 0.0;
+  for (int32_t i = 0; i <= L.n_thr; ++i) {
+    const double cur = (i < L.n_thr) ? static_cast<double>(L.thr[i]) : two32;
+    const double pr = (cur - prev) / two32;
+    const double v = static_cast<double>(L.lo) + i;
+    m1 += pr * v;
+    m2 += pr * v * v;
+    prev = cur;
+  }
+}
+
+int sync_last(fcs_engine* h) {
+  return hipStreamSynchronize(static_cast<hipStream_t>(h->run_stream)) == hipSuccess ? FCS_OK : FCS_EDEVICE;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fcs_create(const fcs_params* p, fcs_handle* out) {
+  if (!out) return FCS_EINVAL;
+  *out = nullptr;
+  if (!params_ok(p)) return FCS_EINVAL;
+  fcs_engine* h = new (std::nothrow) fcs_engine();
+  if (!h) return FCS_ENOMEM;
+  h->M = p->capacity; h->tau = p->token_budget; h->chunk = p->prefill_chunk;
+  h->n_classes = p->n_classes; h->n_arrival_laws = p->n_arrival_laws; h->n_cells = p->n_cells;
+  h->trace_every = p->trace_every; h->hist_bins = p->hist_bins; h->hist_shift = p->hist_shift;
+  h->max_requests = p->max_requests; h->max_active = p->max_active; h->lds_slots_param = p->lds_slots;
+  h->l_min = p->prompt[0].lo;
+  for (int32_t c = 1; c < p->n_classes; ++c) h->l_min = std::min(h->l_min, p->prompt[c].lo);
+
+  // blob: [DLaw x n_laws][DCell x n_cells][class thresholds][thresholds and guides]
+  const int n_laws = p->n_arrival_laws + 2 * p->n_classes;
+  std::vector<uint32_t> body;
+  std::vector<DLaw> laws;
+  const uint32_t head_words = static_cast<uint32_t>(4 * n_laws + 4 * p->n_cells + std::max(p->n_classes - 1, 0));
+  for (int32_t a = 0; a < p->n_arrival_laws; ++a) append_law(body, laws, p->arrival[a], false);
+  for (int32_t c = 0; c < p->n_classes; ++c) append_law(body, laws, p->prompt[c], true);
+  for (int32_t c = 0; c < p->n_classes; ++c) append_law(body, laws, p->decode[c], true);
+  for (DLaw& d : laws) { d.off += head_words; if (d.goff) d.goff += head_words; }
+  h->laws_off = 0;
+  h->cells_off = static_cast<uint32_t>(4 * n_laws);
+  h->class_off = h->cells_off + static_cast<uint32_t>(4 * p->n_cells);
+  h->blob.resize(head_words);
+  std::memcpy(h->blob.data(), laws.data(), sizeof(DLaw) * laws.size());
+  for (int32_t i = 0; i < p->n_cells; ++i) {
+    DCell d{p->cells[i].policy, p->cells[i].arrival, p->cells[i].b_floor, p->cells[i].b_frac_thr};
+    h->cells.push_back(d);
+    std::memcpy(h->blob.data() + h->cells_off + 4 * i, &d, sizeof(d));
+  }
+  for (int32_t c = 0; c + 1 < p->n_classes; ++c) h->blob[h->class_off + c] = p->class_thr[c];
+  h->blob.insert(h->blob.end(), body.begin(), body.end());
+  h->blob_bytes_padded = round_up(h->blob.size() * sizeof(uint32_t), 256);
+  *out = h;
+  return FCS_OK;
+}
+
+static int geometry_for(fcs_engine* h, int64_t n_replicas, int32_t* lcap, int32_t* hcap, int32_t* hscap) {
+  if (n_replicas < 1) return FCS_EINVAL;
+  const int64_t n_paths = n_replicas * h->n_cells;
+  if (n_paths > (1ll << 30)) return FCS_EINVAL;
+  int64_t max_active = h->max_active;
+  if (max_active == 0) max_active = std::min<int64_t>(h->M / (h->l_min + 1) + 1, 8192);
+  max_active = static_cast<int64_t>(round_up(static_cast<size_t>(max_active), kWave));
+  int32_t lc = h->lds_slots_param;
+  if (lc == 0) {
+    // spread the paths over the 256 compute units and give each wavefront an equal share of
+    // the 160 KB of LDS, between 4 and 12 wavefronts per unit
+    int64_t per_cu = (n_paths + 255) / 256;
+    per_cu = std::min<int64_t>(std::max<int64_t>(per_cu, 4), 12);
+    const int64_t words = (160 * 1024 / per_cu) / 4 - S_NFIELDS * kStackLds - kScratchWords;
+    lc = static_cast<int32_t>(words / F_NFIELDS / kLdsBlock * kLdsBlock);
+    lc = std::min(std::max(lc, kLdsBlock), 2048);
+  }
+  lc = static_cast<int32_t>(std::min<int64_t>(lc, static_cast<int64_t>(round_up(max_active, kLdsBlock))));
+  *lcap = lc;
+  *hcap = static_cast<int32_t>(std::max<int64_t>(max_active - lc, 0));
+  *hscap = static_cast<int32_t>(std::max<int64_t>(max_active - kStackLds, 0));
+  return FCS_OK;
+}
+
+int fcs_workspace_bytes(fcs_handle h, int64_t n_replicas, size_t* bytes) {
+  if (!h || !bytes) return FCS_EINVAL;
+  int32_t lc, hc, hs;
+  int rc = geometry_for(h, n_replicas, &lc, &hc, &hs);
+  if (rc != FCS_OK) return rc;
+  const size_t stride = static_cast<size_t>(F_NFIELDS) * hc + static_cast<size_t>(S_NFIELDS) * hs;
+  *bytes = h->blob_bytes_padded + round_up(stride * sizeof(int32_t) * n_replicas * h->n_cells, 256) + 256;
+  return FCS_OK;
+}
+
+int fcs_bind(fcs_handle h, void* ws, size_t bytes, int64_t n_replicas, const fcs_outputs* o, void* stream) {
+  if (!h || !ws || !o || !o->counters) return FCS_EINVAL;
+  if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return FCS_EINVAL;
+  size_t need = 0;
+  int rc = fcs_workspace_bytes(h, n_replicas, &need);
+  if (rc != FCS_OK) return rc;
+  if (bytes < need) return FCS_ENOMEM;
+  rc = geometry_for(h, n_replicas, &h->lcap, &h->hcap, &h->hscap);
+  if (rc != FCS_OK) return rc;
+  h->spill_stride = static_cast<int64_t>(F_NFIELDS) * h->hcap + static_cast<int64_t>(S_NFIELDS) * h->hscap;
+  hipError_t e = hipMemcpyAsync(ws, h->blob.data(), h->blob.size() * sizeof(uint32_t),
+                                hipMemcpyHostToDevice, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return FCS_EDEVICE;
+  // the blob is pageable host memory owned by the handle: wait so it may change afterwards
+  if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return FCS_EDEVICE;
+  h->workspace = ws;
+  h->workspace_bytes = bytes;
+  h->bound_replicas = n_replicas;
+  h->out = *o;
+  h->bound = true;
+  h->ran = false;
+  return FCS_OK;
+}
+
+int fcs_run_from(fcs_handle h, int64_t replica_base, int64_t n_replicas, int64_t n_steps, uint64_t seed,
+                 void* stream) {
+  if (!h) return FCS_EINVAL;
+  if (!h->bound) return FCS_ESTATE;
+  if (n_replicas < 1 || n_replicas > h->bound_replicas) return FCS_EINVAL;
+  if (n_steps < 1 || n_steps >= kLimit) return FCS_EINVAL;
+  if (replica_base < 0 || replica_base + n_replicas > 0xffffffffll) return FCS_EINVAL;
+  if (h->trace_every > 0 && (h->out.trace_q || h->out.trace_u) && n_steps / h->trace_every < 0)
+    return FCS_EINVAL;
+  KParams kp{};
+  kp.blob = static_cast<const uint32_t*>(h->workspace);
+  kp.laws_off = h->laws_off; kp.cells_off = h->cells_off; kp.class_off = h->class_off;
+  kp.n_arrival_laws = h->n_arrival_laws; kp.n_classes = h->n_classes; kp.n_cells = h->n_cells;
+  kp.M = h->M; kp.tau = h->tau; kp.chunk = h->chunk;
+  kp.n_replicas = static_cast<int32_t>(n_replicas);
+  kp.replica_base = static_cast<uint32_t>(replica_base);
+  kp.n_steps = static_cast<int32_t>(n_steps);
+  kp.seed_lo = static_cast<uint32_t>(seed);
+  kp.seed_hi = static_cast<uint32_t>(seed >> 32);
+  kp.lcap = h->lcap; kp.hcap = h->hcap; kp.hscap = h->hscap;
+  kp.spill = reinterpret_cast<int32_t*>(static_cast<char*>(h->workspace) + h->blob_bytes_padded);
+  kp.spill_stride = h->spill_stride;
+  kp.trace_every = h->trace_every;
+  kp.n_trace = h->trace_every > 0 ? static_cast<int32_t>(n_steps / h->trace_every) : 0;
+  kp.hist_bins = h->hist_bins; kp.hist_shift = h->hist_shift; kp.max_requests = h->max_requests;
+  kp.n_paths = static_cast<int32_t>(n_replicas * h->n_cells);
+  kp.out = h->out;
+  if (h->hist_bins == 0) kp.out.hist = nullptr;
+  if (h->max_requests == 0) { kp.out.arrival_step = nullptr; kp.out.completion_step = nullptr; }
+  if (h->trace_every == 0) { kp.out.trace_q = nullptr; kp.out.trace_u = nullptr; }
+  int rc = launch_sim(kp, stream);
+  if (rc != FCS_OK) return rc;
+  h->ran = true;
+  h->run_replicas = n_replicas;
+  h->run_steps = n_steps;
+  h->run_stream = stream;
+  return FCS_OK;
+}
+
+int fcs_run(fcs_handle h, int64_t n_replicas, int64_t n_steps, uint64_t seed, void* stream) {
+  return fcs_run_from(h, 0, n_replicas, n_steps, seed, stream);
+}
+
+int fcs_stats(fcs_handle h, int32_t cell, uint64_t* host_counters, fcs_summary* s) {
+  if (!h) return FCS_EINVAL;
+  if (!h->ran) return FCS_ESTATE;
+  if (cell < -1 || cell >= h->n_cells) return FCS_EINVAL;
+  int rc = sync_last(h);
+  if (rc != FCS_OK) return rc;
+  const int64_t n_paths = h->run_replicas * h->n_cells;
+  std::vector<uint64_t> local;
+  uint64_t* C = host_counters;
+  if (!C) {
+    local.resize(static_cast<size_t>(n_paths) * FCS_N_COUNTERS);
+    C = local.data();
+  }
+  if (hipMemcpy(C, h->out.counters, sizeof(uint64_t) * n_paths * FCS_N_COUNTERS, hipMemcpyDeviceToHost) !=
+      hipSuccess)
+    return FCS_EDEVICE;
+  int64_t first_err = -1;
+  int32_t err_code = 0;
+  for (int64_t p = 0; p < n_paths; ++p) {
+    if (C[p * FCS_N_COUNTERS + FCS_C_ERROR] != 0 && first_err < 0) {
+      first_err = p;
+      err_code = -static_cast<int32_t>(C[p * FCS_N_COUNTERS + FCS_C_ERROR]);
+    }
+  }
+  if (s) {
+    std::memset(s, 0, sizeof(*s));
+    const int64_t lo = cell < 0 ? 0 : cell * h->run_replicas;
+    const int64_t hi = cell < 0 ? n_paths : lo + h->run_replicas;
+    uint64_t sum_u = 0, sum_q = 0, sum_lat = 0, useful = 0;
+    for (int64_t p = lo; p < hi; ++p) {
+      const uint64_t* c = C + p * FCS_N_COUNTERS;
+      s->request_steps += c[FCS_C_SUM_P];
+      s->arrived += c[FCS_C_ARRIVED];
+      s->completed += c[FCS_C_COMPLETED];
+      s->evictions += c[FCS_C_EVICTIONS];
+      s->overflow_steps += c[FCS_C_OVERFLOW_STEPS];
+      sum_u += c[FCS_C_SUM_U];
+      sum_q += c[FCS_C_SUM_Q];
+      sum_lat += c[FCS_C_SUM_LATENCY];
+      useful += c[FCS_C_USEFUL_TOKENS];
+    }
+    s->n_paths = hi - lo;
+    s->n_steps = h->run_steps;
+    const double slots = static_cast<double>(s->n_paths) * static_cast<double>(h->run_steps);
+    s->mean_latency = s->completed ? static_cast<double>(sum_lat) / static_cast<double>(s->completed) : 0.0;
+    s->kv_utilisation = static_cast<double>(sum_u) / (slots * static_cast<double>(h->M));
+    s->token_throughput = static_cast<double>(useful) / slots;
+    s->prompt_throughput = static_cast<double>(s->completed) / slots;
+    s->mean_queue = static_cast<double>(sum_q) / slots;
+    s->mean_active = static_cast<double>(s->request_steps) / slots;
+    s->first_error_path = first_err;
+    s->error_code = err_code;
+  }
+  return first_err >= 0 ? FCS_EOVERFLOW : FCS_OK;
+}
+
+int fcs_percentile(fcs_handle h, int64_t num, int64_t den, int32_t* value, uint8_t* saturated) {
+  if (!h || !value || den < 1 || num < 0 || num > den) return FCS_EINVAL;
+  if (!h->ran || h->hist_bins == 0 || !h->out.hist) return FCS_ESTATE;
+  int rc = sync_last(h);
+  if (rc != FCS_OK) return rc;
+  const int64_t n_paths = h->run_replicas * h->n_cells;
+  const int64_t bins = h->hist_bins;
+  const int64_t batch = std::max<int64_t>(1, (64ll << 20) / (bins * 4));
+  std::vector<uint32_t> buf(static_cast<size_t>(std::min(batch, n_paths) * bins));
+  for (int64_t p0 = 0; p0 < n_paths; p0 += batch) {
+    const int64_t np = std::min(batch, n_paths - p0);
+    if (hipMemcpy(buf.data(), h->out.hist + p0 * bins, sizeof(uint32_t) * np * bins, hipMemcpyDeviceToHost) !=
+        hipSuccess)
+      return FCS_EDEVICE;
+    for (int64_t p = 0; p < np; ++p) {
+      const uint32_t* hp = buf.data() + p * bins;
+      uint64_t n = 0;
+      for (int64_t b = 0; b < bins; ++b) n += hp[b];
+      int64_t bucket = 0;
+      if (n > 0) {
+        // nearest rank: the k-th smallest with k = ceil(num * n / den), at least 1
+        __uint128_t prod = static_cast<__uint128_t>(num) * n + static_cast<__uint128_t>(den - 1);
+        uint64_t k = static_cast<uint64_t>(prod / static_cast<__uint128_t>(den));
+        if (k < 1) k = 1;
+        uint64_t cum = 0;
+        for (bucket = 0; bucket < bins; ++bucket) {
+          cum += hp[bucket];
+          if (cum >= k) break;
+        }
+      }
+      value[p0 + p] = static_cast<int32_t>(bucket << h->hist_shift);
+      if (saturated) saturated[p0 + p] = (n > 0 && bucket == bins - 1) ? 1 : 0;
+    }
+  }
+  return FCS_OK;
+}
+
+int fcs_stability_bound(const fcs_params* p, double* lambda_star) {
+  if (!p || !lambda_star) return FCS_EINVAL;
+  if (p->capacity < 1 || p->n_classes < 1 || p->n_classes > kMaxClasses || !p->prompt || !p->decode)
+    return FCS_EINVAL;
+  const double two32 = 4294967296.0;
+  double ew = 0.0, prev = 0.0;
+  for (int32_t c = 0; c < p->n_classes; ++c) {
+    if (!law_ok(p->prompt[c], 0, 1 << 24) || !law_ok(p->decode[c], 0, 1 << 24)) return FCS_EINVAL;
+    const double cur = (c + 1 < p->n_classes) ? static_cast<double>(p->class_thr[c]) : two32;
+    const double pc = (cur - prev) / two32;
+    prev = cur;
+    double el, el2, eo, eo2;
+    law_moments(p->prompt[c], el, el2);
+    law_moments(p->decode[c], eo, eo2);
+    ew += pc * (el * eo + 0.5 * (eo + eo2));  // E[l o + (o + o^2)/2], l and o independent
+  }
+  if (!(ew > 0.0)) return FCS_EINVAL;
+  *lambda_star = static_cast<double>(p->capacity) / ew;
+  return FCS_OK;
+}
+
+int fcs_geometry(fcs_handle h, int32_t* lds_slots, int32_t* lds_bytes, int32_t* spill_slots) {
+  if (!h) return FCS_EINVAL;
+  if (!h->bound) return FCS_ESTATE;
+  if (lds_slots) *lds_slots = h->lcap;
+  if (lds_bytes) *lds_bytes = lds_words(h->lcap) * 4;
+  if (spill_slots) *spill_slots = h->hcap;
+  return FCS_OK;
+}
+
+void fcs_destroy(fcs_handle h) { delete h; }
+
+const char* fcs_strerror(int code) {
+  switch (code) {
+    case FCS_OK: return "ok";
+    case FCS_EINVAL: return "invalid argument";
+    case FCS_ENOMEM: return "workspace too small or out of host memory";
+    case FCS_ESTATE: return "call out of order";
+    case FCS_EOVERFLOW: return "a path outgrew its active-set capacity";
+    case FCS_EDEVICE: return "HIP error or no device";
+    default: return "unknown error";
+  }
+}
+
+int fcs_n_counters(void) { return FCS_N_COUNTERS; }
+
+const char* fcs_counter_name(int i) {
+  static const char* const names[FCS_N_COUNTERS] = {
+      "arrived", "activations", "completed", "evictions", "overflow_steps", "sum_u", "sum_p", "sum_q",
+      "decode_tokens", "prefill_tokens", "useful_tokens", "stalled", "sum_latency", "max_latency",
+      "max_u", "max_p", "max_q", "final_u", "final_p", "final_q", "digest", "error", "error_step",
+      "reserved"};
+  return (i >= 0 && i < FCS_N_COUNTERS) ? names[i] : nullptr;
+}
+
+}  // extern "C"

@@ -1,0 +1,64 @@
+// Internal layout shared by the host API and the device kernel of libfcs.
+#ifndef FCS_INTERNAL_H_
+#define FCS_INTERNAL_H_
+
+#include <stdint.h>
+
+#include "fcs.h"
+
+namespace fcs {
+
+// A law as the kernel sees it: thresholds and a 257-entry guide live in the table blob.
+// guide[b] = #{ i : thr[i] < (b << 24) }, so the inversion of a word u lies in
+// [guide[u >> 24], guide[(u >> 24) + 1]].
+struct DLaw {
+  int32_t lo;
+  int32_t n;
+  uint32_t off;   // word offset of thr[] in the blob
+  uint32_t goff;  // word offset of guide[] in the blob (length laws only)
+};
+
+struct DCell {
+  int32_t policy;
+  int32_t arrival;
+  int32_t b_floor;
+  uint32_t b_frac_thr;
+};
+
+// Fields of one active-set slot (structure of arrays, int32 each).
+enum { F_REM = 0, F_PLEFT, F_L, F_O, F_TARR, F_ID, F_NFIELDS };
+// Fields of one entry of the stack of evicted requests.
+enum { S_ID = 0, S_L, S_O, S_TARR, S_NFIELDS };
+
+constexpr int kWave = 64;
+constexpr int kLdsBlock = 256;       // slots per b128 pass over the LDS tier
+constexpr int kStackLds = 64;        // evicted-stack entries kept in LDS
+constexpr int kScratchWords = 64;
+constexpr int kCompactSlack = 64;    // compact when this many dead slots have accumulated
+constexpr int kMaxCountThr = 63;
+constexpr int kMaxClasses = 16;
+
+struct KParams {
+  const uint32_t* blob;
+  uint32_t laws_off, cells_off, class_off;
+  int32_t n_arrival_laws, n_classes, n_cells;
+  int32_t M, tau, chunk;
+  int32_t n_replicas;
+  uint32_t replica_base;
+  int32_t n_steps;
+  uint32_t seed_lo, seed_hi;
+  int32_t lcap, hcap, hscap;  // LDS slots, spill slots, spill stack entries (per path)
+  int32_t* spill;             // per path: F_NFIELDS*hcap + S_NFIELDS*hscap words
+  int64_t spill_stride;       // words per path
+  int32_t trace_every, n_trace, hist_bins, hist_shift, max_requests;
+  int32_t n_paths;
+  fcs_outputs out;
+};
+
+inline int lds_words(int lcap) { return F_NFIELDS * lcap + S_NFIELDS * kStackLds + kScratchWords; }
+
+// Defined in fcs_sim.hip; launches one single-wavefront workgroup per path.
+int launch_sim(const KParams& kp, void* stream);
+
+}  // namespace fcs
+#endif

@@ -1,0 +1,132 @@
+"""GPU parity: the HIP engine, called through the C ABI, against the CPU oracle.
+
+Bar: bit-exact on every integer (counters, traces, histograms, per-request arrival and completion
+slots, final-state digest, nearest-rank percentiles); 1e-9 relative on derived floating point.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2604_11001_amd as fcs
+from workloads import FLOW, GREEDY, configs, laws
+from workloads.configs import Workload, flow_cell, greedy_cell
+
+from parity_util import check_summary, compare
+
+pytestmark = pytest.mark.gpu
+
+INF = 1 << 30
+
+
+def run(wl, **kw):
+    eng = fcs.Engine(wl, **kw)
+    eng.run()
+    return eng
+
+
+def test_toy_eviction_heavy_both_policies():
+    for wl in (configs.toy(), configs.toy(capacity=300, token_budget=40, prefill_chunk=8, lam=0.9, b=1.5, seed=12)):
+        eng = run(wl)
+        got, _, ref = compare(eng, wl, label=wl.name)
+        check_summary(eng, wl, got)
+        assert got["evictions"].sum() > 0 and got["stalled"].sum() > 0
+
+
+def test_hand_trajectory_shapes_via_point_laws():
+    # paper's synthetic classes (Section 4.1), overloaded and stable, both policies
+    for lam in (5.0, 3.0):
+        wl = configs.three_class(lam, n_replicas=8, n_steps=1500)
+        compare(run(wl), wl, label=f"three-class {lam}")
+
+
+def test_config0_full():
+    wl = configs.config0(oracle.stability_bound)
+    eng = run(wl)
+    got, summary, _ = compare(eng, wl, label="cfg0")
+    check_summary(eng, wl, got)
+    assert summary["request_steps"] > 3_000_000
+
+
+def _big_active(n_replicas=6, n_steps=3000, **kw):
+    mix = laws.single(laws.uniform_int(1, 8), laws.geometric(40.0, cap=200))
+    return Workload(name="big-active", capacity=40000, token_budget=2000, prefill_chunk=4, mixture=mix,
+                    arrival_laws=(laws.poisson_counts(10.0),), cells=(flow_cell(0, 10.6), greedy_cell(0)),
+                    n_replicas=n_replicas, n_steps=n_steps, seed=5, trace_every=100, hist_bins=512,
+                    max_requests=1 << 15, **kw)
+
+
+def test_active_set_spills_past_lds():
+    wl = _big_active()
+    eng = run(wl, lds_slots=256, max_active=2048)
+    got, _, _ = compare(eng, wl, label="spill")
+    assert got["max_p"].max() > 300          # the spill tier was really used
+    eng2 = run(wl, lds_slots=1024, max_active=2048)
+    got2, _ = eng2.stats()
+    for k in got:
+        assert np.array_equal(got[k], got2[k]), k
+
+
+def test_overflowing_capacity_is_reported_not_fatal():
+    wl = _big_active(n_replicas=2, n_steps=500)
+    eng = run(wl, lds_slots=256, max_active=256)
+    with pytest.raises(fcs.FcsError) as e:
+        eng.stats()
+    assert e.value.code == -4
+    got, s = eng.stats(allow_overflow=True)
+    assert np.all(got["error"] == 4) and s["first_error_path"] == 0 and s["error_code"] == -4
+
+
+def test_edge_cases():
+    # one slot; horizon not a multiple of the draw window; no arrivals at all; record arrays too short
+    base = configs.toy(n_replicas=3)
+    for T in (1, 63, 64, 65, 129):
+        wl = base.scaled(n_steps=T)
+        compare(run(wl), wl, label=f"T={T}")
+    quiet = configs.toy(n_replicas=2, n_steps=200)
+    quiet = quiet.scaled(arrival_laws=(laws.poisson_counts(0.0),))
+    eng = run(quiet)
+    got, _, _ = compare(eng, quiet, label="no arrivals")
+    assert got["arrived"].sum() == 0 and got["sum_p"].sum() == 0
+    short = configs.toy(n_replicas=2, n_steps=400, max_requests=64)
+    got, _, _ = compare(run(short), short, label="short record arrays")
+    assert got["arrived"].min() > 64
+
+
+def test_replica_base_shards_a_sweep():
+    wl = configs.toy(n_replicas=8, n_steps=300)
+    whole = run(wl)
+    a, _ = whole.stats()
+    part = fcs.Engine(wl, n_replicas=4)
+    part.run(replica_base=4)
+    b, _ = part.stats()
+    for ci in range(2):
+        for k in ("sum_u", "digest", "completed"):
+            assert np.array_equal(a[k][ci * 8 + 4: ci * 8 + 8], b[k][ci * 4: ci * 4 + 4]), k
+
+
+def test_config1_scaled_and_both_policies_share_arrivals():
+    wl = configs.config1(oracle.stability_bound).scaled(n_replicas=24, n_steps=30000, max_requests=1 << 15,
+                                                        hist_bins=2048, hist_shift=3)
+    eng = run(wl)
+    got, _, _ = compare(eng, wl, replica_ids=[0, 5, 23], label="cfg1 scaled")
+    assert np.array_equal(got["arrived"][:24], got["arrived"][24:])
+    check_summary(eng, wl, got)
+
+
+def test_config2_scaled_traces():
+    wl = configs.config2(oracle.stability_bound).scaled(n_replicas=8, n_steps=20000)
+    eng = run(wl)
+    compare(eng, wl, replica_ids=[0, 7], label="cfg2 scaled")
+
+
+def test_config3_scaled_grid_percentiles():
+    wl = configs.config3(oracle.stability_bound, n_lambda=4, n_b=3).scaled(n_replicas=6, n_steps=8000)
+    eng = run(wl)
+    got, _, _ = compare(eng, wl, replica_ids=[1, 4], label="cfg3 scaled")
+    check_summary(eng, wl, got)
+
+
+def test_config4_scaled_with_and_without_spill():
+    wl = configs.config4(oracle.stability_bound).scaled(n_replicas=6, n_steps=40000)
+    compare(run(wl), wl, replica_ids=[0, 3], label="cfg4 scaled")
+    compare(run(wl, lds_slots=256), wl, replica_ids=[0, 3], label="cfg4 scaled, small LDS tile")

@@ -1,0 +1,90 @@
+"""Host-side checks that need no GPU: the library loads, exports its ABI, validates parameters."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2604_11001_amd as fcs
+from paper_2604_11001_amd import binding
+from workloads import configs, laws
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    with open(os.path.join(ROOT, "include", "fcs.h")) as f:
+        text = f.read()
+    declared = set(re.findall(r"\b(fcs_[a-z_]+)\s*\(", text))
+    assert declared == set(binding.EXPORTS)
+    L = fcs.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_counter_names_cover_the_oracle():
+    names = fcs.counter_names()
+    assert len(names) == fcs.lib().fcs_n_counters() and len(set(names)) == len(names)
+    assert set(oracle.counter_names()) <= set(names)
+
+
+def test_stability_bound_matches_the_oracle_closed_form():
+    for i in range(5):
+        wl = configs.make(i, oracle.stability_bound)
+        a = oracle.stability_bound(wl.mixture, wl.capacity)
+        b = fcs.stability_bound(wl.mixture, wl.capacity)
+        assert abs(a - b) <= 1e-12 * a
+    assert abs(fcs.stability_bound(configs.three_class(1.0).mixture, 16492) - 3 * 16492 / 4060.0) < 1e-7   # class weights are quantised to 2^-32
+
+
+def _create(wl, **kw):
+    p, keep = binding.make_params(wl, **kw)
+    h = C.c_void_p()
+    rc = fcs.lib().fcs_create(C.byref(p), C.byref(h))
+    if rc == 0:
+        fcs.lib().fcs_destroy(h)
+    return rc
+
+
+def test_create_validates_parameters():
+    ok = configs.toy()
+    assert _create(ok) == 0
+    assert _create(ok.scaled(capacity=0)) == -1
+    assert _create(ok.scaled(token_budget=0)) == -1
+    assert _create(ok.scaled(prefill_chunk=0)) == -1
+    assert _create(ok.scaled(capacity=100)) == -1            # max l + max o = 140 > M
+    assert _create(ok, lds_slots=100) == -1
+    bad = laws.Law.__new__(laws.Law)
+    object.__setattr__(bad, "lo", 1)
+    object.__setattr__(bad, "thr", np.array([5, 3], np.uint32))
+    object.__setattr__(bad, "name", "decreasing")
+    assert _create(ok.scaled(mixture=laws.single(bad, laws.point(3)))) == -1
+    assert _create(ok.scaled(mixture=laws.single(laws.point(0), laws.point(3)))) == -1   # l >= 1
+    assert _create(ok.scaled(cells=(configs.Cell(7, 0, 0, 0),))) == -1
+    assert _create(ok.scaled(cells=(configs.Cell(0, 3, 0, 0),))) == -1
+    assert _create(ok.scaled(arrival_laws=(laws.uniform_int(0, 100),))) == -1            # > 63 thresholds
+
+
+def test_calls_out_of_order_and_null_arguments():
+    L = fcs.lib()
+    p, keep = binding.make_params(configs.toy())
+    h = C.c_void_p()
+    assert L.fcs_create(C.byref(p), C.byref(h)) == 0
+    n = C.c_size_t(0)
+    assert L.fcs_workspace_bytes(h, 16, C.byref(n)) == 0 and n.value > 0
+    assert L.fcs_workspace_bytes(h, 0, C.byref(n)) == -1
+    assert L.fcs_run(h, 16, 100, 1, None) == -3            # not bound
+    assert L.fcs_stats(h, -1, None, None) == -3            # nothing ran
+    assert L.fcs_create(None, C.byref(h)) == -1
+    assert L.fcs_strerror(-4).decode().startswith("a path outgrew")
+    L.fcs_destroy(h)
+
+
+def test_engine_refuses_to_run_without_a_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(RuntimeError):
+        fcs.Engine(configs.toy())
