@@ -1,0 +1,130 @@
+#!/usr/bin/env python3
+"""Benchmark of the sample-path engine on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input: one
+``fcs_run`` of the flow-control-versus-greedy workload (1,024 replicas x 100,000
+slots, both policies on identical random streams), tables already resident in HBM.
+Prints ONE JSON line: simulated request-steps per second (sum over paths and slots
+of |P_t|), the HBM-roofline reading of the kernel (algorithmic bytes = 8 B per
+request-step: one read and one write of the per-request token counter), and the
+CPU oracle timed on a bounded sample of the same workload on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+BYTES_PER_REQUEST_STEP = 8.0
+HBM_PEAK_GBS = 8000.0
+
+
+def cpu_baseline(config_index: int, target_seconds: float = 15.0):
+    """Times the oracle as it stands on a bounded sample: a few replicas of every cell, full horizon."""
+    import numpy as np
+
+    import oracle
+    from workloads import configs
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")))
+    wl = configs.make(config_index, oracle.stability_bound)
+    oracle.lib()
+    # calibrate on one replica per cell, then size the sample for about target_seconds
+    t0 = time.perf_counter()
+    rs = 0
+    for ci in range(len(wl.cells)):
+        rs += int(oracle.run_cell(wl, ci, replica_ids=[0], n_threads=1)["counters"]["sum_p"].sum())
+    one = time.perf_counter() - t0
+    n_rep = int(max(cores, min(wl.n_replicas, cores * max(1, round(target_seconds / max(one, 1e-3))))))
+    n_rep = (n_rep // cores) * cores
+    ids = np.arange(n_rep)
+    t0 = time.perf_counter()
+    total = 0
+    for ci in range(len(wl.cells)):
+        total += int(oracle.run_cell(wl, ci, replica_ids=ids, n_threads=cores)["counters"]["sum_p"].sum())
+    dt = time.perf_counter() - t0
+    return {"value": total / dt, "unit": "request-steps/s", "cores": cores, "kind": "oracle",
+            "sample": f"{n_rep} of {wl.n_replicas} replicas x {wl.n_steps} slots x {len(wl.cells)} cells "
+                      f"({total} request-steps in {dt:.2f} s)"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=1, help="index of the benchmark configuration (default 1)")
+    ap.add_argument("--replicas", type=int, default=None)
+    ap.add_argument("--slots", type=int, default=None)
+    ap.add_argument("--lds-slots", type=int, default=0)
+    ap.add_argument("--max-active", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this engine runs on one GPU; sample paths are independent, so several GPUs would "
+              "each take a share of the replicas with no exchange. Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2604_11001_amd as fcs
+    from workloads import configs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no HIP device", file=sys.stderr)
+        return 3
+    wl = configs.make(args.config, fcs.stability_bound)
+    if args.replicas or args.slots:
+        wl = wl.scaled(n_replicas=args.replicas, n_steps=args.slots)
+    # statistics only: per-request records and histograms are parity-test outputs
+    wl = wl.scaled(max_requests=0)
+    eng = fcs.Engine(wl, max_active=args.max_active, lds_slots=args.lds_slots)
+    geo = eng.geometry()
+
+    for _ in range(args.warmup):
+        eng.run()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record()
+        eng.run()
+        b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernel_ms = [a.elapsed_time(b) for a, b in ev]
+    counters, summary = eng.stats()
+    rs_per_step = int(summary["request_steps"])
+    value = rs_per_step * args.steps / wall
+    avg_kernel_s = sum(kernel_ms) / len(kernel_ms) / 1e3
+    achieved = rs_per_step * BYTES_PER_REQUEST_STEP / avg_kernel_s / 1e9
+
+    line = {
+        "metric": "simulated request-steps/sec (replicas x steps x active reqs); % of HBM roofline",
+        "value": value, "unit": "request-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {wl.name}", "replicas": wl.n_replicas,
+                   "slots": wl.n_steps, "cells": len(wl.cells), "paths": eng.n_paths,
+                   "capacity": wl.capacity, "token_budget": wl.token_budget, "prefill_chunk": wl.prefill_chunk,
+                   "request_steps_per_step": rs_per_step, "lds_slots": geo["lds_slots"],
+                   "lds_bytes_per_path": geo["lds_bytes"], "spill_slots": geo["spill_slots"],
+                   "evictions": int(summary["evictions"]), "completed": int(summary["completed"])},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "fcs_sim_kernel", "kernel_ms": sum(kernel_ms) / len(kernel_ms),
+                     "bytes_per_request_step": BYTES_PER_REQUEST_STEP},
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(args.config)
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
