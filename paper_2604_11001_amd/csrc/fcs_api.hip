@@ -95,11 +95,12 @@ void append_law(std::vector<uint32_t>& blob, std::vector<DLaw>& laws, const fcs_
   d.goff = 0;
   if (guide) {
     d.goff = static_cast<uint32_t>(blob.size());
-    for (uint32_t b = 0; b <= 256; ++b) {
-      // guide[b] = number of thresholds strictly below b << 24 (all of them for b = 256)
+    const uint32_t buckets = 1u << kGuideBits;
+    for (uint32_t b = 0; b <= buckets; ++b) {
+      // guide[b] = number of thresholds strictly below b << (32 - kGuideBits), all of them at the end
       uint32_t cnt;
-      if (b == 256) cnt = static_cast<uint32_t>(L.n_thr);
-      else cnt = static_cast<uint32_t>(std::lower_bound(L.thr, L.thr + L.n_thr, b << 24) - L.thr);
+      if (b == buckets) cnt = static_cast<uint32_t>(L.n_thr);
+      else cnt = static_cast<uint32_t>(std::lower_bound(L.thr, L.thr + L.n_thr, b << (32 - kGuideBits)) - L.thr);
       blob.push_back(cnt);
     }
   }

@@ -8,9 +8,9 @@
 
 namespace fcs {
 
-// A law as the kernel sees it: thresholds and a 257-entry guide live in the table blob.
-// guide[b] = #{ i : thr[i] < (b << 24) }, so the inversion of a word u lies in
-// [guide[u >> 24], guide[(u >> 24) + 1]].
+// A law as the kernel sees it: thresholds and a guide of 2^kGuideBits + 1 entries live in the
+// table blob.  guide[b] = #{ i : thr[i] < (b << (32 - kGuideBits)) }, so the inversion of a word u
+// lies in [guide[u >> (32 - kGuideBits)], guide[(u >> (32 - kGuideBits)) + 1]].
 struct DLaw {
   int32_t lo;
   int32_t n;
@@ -31,6 +31,7 @@ enum { F_REM = 0, F_PLEFT, F_L, F_O, F_TARR, F_ID, F_NFIELDS };
 enum { S_ID = 0, S_L, S_O, S_TARR, S_NFIELDS };
 
 constexpr int kWave = 64;
+constexpr int kGuideBits = 12;
 constexpr int kLdsBlock = 256;       // slots per b128 pass over the LDS tier
 constexpr int kStackLds = 64;        // evicted-stack entries kept in LDS
 constexpr int kScratchWords = 64;

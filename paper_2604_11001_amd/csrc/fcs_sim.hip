@@ -2,19 +2,23 @@
 // model (Section 2.1) under Algorithm 2 or its greedy limit, for slots 1..T.
 //
 // Data layout per path
-//   active set   structure of arrays in activation order with dead slots left in place
-//                ("tombstones"), compacted when kCompactSlack of them have accumulated.
-//                Slots [0, lcap) live in LDS, slots [lcap, lcap+hcap) in a per-path spill
-//                region of the workspace.  F_REM holds o - j for a decoding request and a
-//                negative value otherwise, so the decode growth of a slot (Section 2.1: one
-//                more token per active request) is one decrement per live slot and a
-//                request completes when it reaches zero.
-//   waiting queue  never materialised for requests that were not activated yet: arrivals
-//                are a pure function of (seed, replica, slot, index), so the FIFO of fresh
-//                requests is re-generated, 64 arrivals at a time, when they are admitted.
-//                Evicted requests (which re-enter at the front, newest eviction deepest)
-//                form a stack: first kStackLds entries in LDS, the rest in the spill region.
-//   scalars      usage U, |P|, counts and all statistics stay in scalar registers.
+//   active set   slots in activation order; completed requests leave dead slots behind
+//                ("tombstones") that an order-preserving compaction removes once kCompactSlack
+//                of them have accumulated.  Slots [0, lcap) live in LDS, slots
+//                [lcap, lcap+hcap) in a per-path spill region of the workspace.  Per slot:
+//                  REM    o - j while decoding, negative otherwise.  The decode growth of a
+//                         slot (Section 2.1: one more token per active request) is one
+//                         decrement per slot of this array, four slots per lane per pass;
+//                         a request completes when its entry reaches zero.
+//                  PLEFT  prompt tokens still to prefill (0 once decoding, 0 for tombstones)
+//                  REC    {l, o, arrival slot, id}, read when the request completes or is evicted
+//   waiting queue  requests that were never activated are not stored: arrivals are a pure
+//                function of (seed, replica, slot, index), so the FIFO of fresh requests is
+//                re-generated 64 arrivals at a time when they are admitted.  Evicted requests
+//                re-enter at the front of Q, newest eviction deepest: a stack (first
+//                kStackLds entries in LDS, the rest in the spill region).
+//   scalars      U, |P|, cursors and counts are wave-uniform and stay in scalar registers;
+//                statistics accumulate in lanes of a few vector registers.
 #include <hip/hip_runtime.h>
 
 #include "fcs_internal.h"
@@ -45,29 +49,15 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
   r0 = c0; r1 = c1; r2 = c2; r3 = c3;
 }
 
-__device__ __forceinline__ int lane_id() { return static_cast<int>(threadIdx.x); }
-
 __device__ __forceinline__ int rfl(int v) { return __builtin_amdgcn_readfirstlane(v); }
-
-__device__ __forceinline__ int wave_incl_sum(int v) {
-  const int lane = lane_id();
-#pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) {
-    const int o = __shfl_up(v, d, kWave);
-    if (lane >= d) v += o;
-  }
+__device__ __forceinline__ int rdl(int v, int l) { return __builtin_amdgcn_readlane(v, l); }
+// lane `l` (a constant) of v takes the wave-uniform value s
+template <int l>
+__device__ __forceinline__ int wrl_c(int s, int v) {
+  asm("v_writelane_b32 %0, %1, %2" : "+v"(v) : "s"(s), "n"(l));
   return v;
 }
-
-__device__ __forceinline__ int wave_incl_max(int v) {
-  const int lane = lane_id();
-#pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) {
-    const int o = __shfl_up(v, d, kWave);
-    if (lane >= d) v = max(v, o);
-  }
-  return v;
-}
+#define wrl(s, l, v) wrl_c<l>((s), (v))
 
 // Lanes of the wavefront exchange data through LDS and the spill region (lane 0 writes a slot
 // that lane k reads later).  To the compiler each lane is a separate thread, so every such
@@ -79,14 +69,41 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+__device__ __forceinline__ int wave_incl_sum(int v, int lane) {
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    const int o = __shfl_up(v, d, kWave);
+    if (lane >= d) v += o;
+  }
+  return v;
+}
+
+__device__ __forceinline__ int wave_incl_max(int v, int lane) {
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    const int o = __shfl_up(v, d, kWave);
+    if (lane >= d) v = max(v, o);
+  }
+  return v;
+}
+
 __device__ __forceinline__ int lanes_below(uint64_t mask) {
   return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
                                    __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
 }
 
+__device__ __forceinline__ uint32_t umin4(v4i v) {
+  return min(min(static_cast<uint32_t>(v.x), static_cast<uint32_t>(v.y)),
+             min(static_cast<uint32_t>(v.z), static_cast<uint32_t>(v.w)));
+}
+
+// lanes of the per-slot statistics vector
+enum { SL_SUM_U = 0, SL_SUM_P, SL_SUM_Q, SL_DEC_TOK, SL_ACT, SL_DONE, SL_EVICT, SL_OVF, SL_PF_TOK,
+       SL_STALLED, SL_COUNT };
+
 __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   extern __shared__ int32_t smem[];
-  const int lane = lane_id();
+  const int lane = static_cast<int>(threadIdx.x);
   const int path = static_cast<int>(blockIdx.x);
   if (path >= kp.n_paths) return;
 
@@ -94,55 +111,61 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   const uint32_t rep = kp.replica_base + static_cast<uint32_t>(path - cell_i * kp.n_replicas);
   const DLaw* __restrict__ laws = reinterpret_cast<const DLaw*>(kp.blob + kp.laws_off);
   const DCell cellp = reinterpret_cast<const DCell*>(kp.blob + kp.cells_off)[cell_i];
-  const DLaw arr = laws[cellp.arrival];
-  const uint32_t* __restrict__ arr_thr = kp.blob + arr.off;
-  const uint32_t* __restrict__ class_thr = kp.blob + kp.class_off;
   const bool greedy = cellp.policy == FCS_POLICY_GREEDY;
   const int M = kp.M, T = kp.n_steps;
   const int LC = kp.lcap, HC = kp.hcap, HS = kp.hscap;
   const int CAP = LC + HC;            // slots of the active set
   const int SCAP = kStackLds + HS;    // entries of the evicted stack
-  int32_t* __restrict__ hA = kp.spill + static_cast<size_t>(path) * kp.spill_stride;
-  int32_t* __restrict__ hS = hA + static_cast<size_t>(F_NFIELDS) * HC;
-  const int S_OFF = F_NFIELDS * LC;
-  const int SCR = S_OFF + S_NFIELDS * kStackLds;
+  // LDS word offsets
+  const int O_PL = LC, O_REC = 2 * LC, O_STK = F_NFIELDS * LC, O_SCR = O_STK + S_NFIELDS * kStackLds;
+  // spill region of this path
+  int32_t* __restrict__ hREM = kp.spill + static_cast<size_t>(path) * kp.spill_stride;
+  int32_t* __restrict__ hPL = hREM + HC;
+  int32_t* __restrict__ hREC = hPL + HC;
+  int32_t* __restrict__ hSTK = hREM + static_cast<size_t>(F_NFIELDS) * HC;
 
-  // ---- tiered accessors ------------------------------------------------------
-  auto a_get = [&](int f, int pos) -> int32_t {
-    return pos < LC ? smem[f * LC + pos] : hA[static_cast<size_t>(f) * HC + (pos - LC)];
+  // ---- record accessors (uniform position: every lane reads the same record) ---------
+  auto rec_load = [&](int pos) -> v4i {
+    if (pos < LC) return *reinterpret_cast<const v4i*>(&smem[O_REC + 4 * pos]);
+    return *reinterpret_cast<const v4i*>(&hREC[4 * static_cast<size_t>(pos - LC)]);
   };
-  auto a_set = [&](int f, int pos, int32_t v) {
-    if (pos < LC) smem[f * LC + pos] = v;
-    else hA[static_cast<size_t>(f) * HC + (pos - LC)] = v;
+  auto slot_store = [&](int pos, int rem, int pleft, v4i rec) {  // executed by one lane
+    if (pos < LC) {
+      smem[pos] = rem;
+      smem[O_PL + pos] = pleft;
+      *reinterpret_cast<v4i*>(&smem[O_REC + 4 * pos]) = rec;
+    } else {
+      const size_t q = static_cast<size_t>(pos - LC);
+      hREM[q] = rem;
+      hPL[q] = pleft;
+      *reinterpret_cast<v4i*>(&hREC[4 * q]) = rec;
+    }
   };
-  auto s_get = [&](int f, int d) -> int32_t {
-    return d < kStackLds ? smem[S_OFF + f * kStackLds + d]
-                         : hS[static_cast<size_t>(f) * HS + (d - kStackLds)];
+  auto rem_pl_load = [&](int pos, int& rem, int& pl) {
+    if (pos < LC) { rem = smem[pos]; pl = smem[O_PL + pos]; }
+    else { rem = hREM[pos - LC]; pl = hPL[pos - LC]; }
   };
-  auto s_set = [&](int f, int d, int32_t v) {
-    if (d < kStackLds) smem[S_OFF + f * kStackLds + d] = v;
-    else hS[static_cast<size_t>(f) * HS + (d - kStackLds)] = v;
+  auto rem_pl_store = [&](int pos, int rem, int pl) {
+    if (pos < LC) { smem[pos] = rem; smem[O_PL + pos] = pl; }
+    else { hREM[pos - LC] = rem; hPL[pos - LC] = pl; }
   };
 
-  // ---- output rows of this path ------------------------------------------------
+  // ---- output rows of this path ------------------------------------------------------
   uint32_t* hist = kp.out.hist ? kp.out.hist + static_cast<size_t>(path) * kp.hist_bins : nullptr;
   int32_t* arr_rec = kp.out.arrival_step
                          ? kp.out.arrival_step + static_cast<size_t>(path) * kp.max_requests : nullptr;
   int32_t* comp_rec = kp.out.completion_step
                           ? kp.out.completion_step + static_cast<size_t>(path) * kp.max_requests : nullptr;
-  int32_t* trq = kp.out.trace_q ? kp.out.trace_q + static_cast<size_t>(path) * kp.n_trace : nullptr;
-  int32_t* tru = kp.out.trace_u ? kp.out.trace_u + static_cast<size_t>(path) * kp.n_trace : nullptr;
   if (hist) for (int i = lane; i < kp.hist_bins; i += kWave) hist[i] = 0u;
   if (arr_rec) for (int i = lane; i < kp.max_requests; i += kWave) arr_rec[i] = 0;
   if (comp_rec) for (int i = lane; i < kp.max_requests; i += kWave) comp_rec[i] = 0;
-  wave_sync();
   for (int i = lane; i < LC; i += kWave) {
-    smem[F_REM * LC + i] = -1;
-    smem[F_PLEFT * LC + i] = 0;
+    smem[i] = -1;
+    smem[O_PL + i] = 0;
   }
   wave_sync();
 
-  // ---- state (wave-uniform) ----------------------------------------------------
+  // ---- state (wave-uniform) ------------------------------------------------------------
   int U = 0;           // sum over P of (l + j)
   int n_live = 0;      // |P|
   int n_dec = 0;       // requests of P that are decoding
@@ -151,19 +174,21 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   int pf_first = 0;    // no prefilling request sits below this slot
   int sdepth = 0;      // evicted requests waiting at the front of Q
   uint32_t arrived = 0, fresh_next = 0;  // arrivals so far; id of the next never-activated request
+  int head_l = -1;     // GREEDY: prompt length of the head of Q, -1 = not fetched
   int err = 0, err_step = 0;
-
   // fresh-request block: lane i holds arrival fb_base + i
   int fb_l = 0, fb_o = 0, fb_t = 0;
   uint32_t fb_base = 0;
   int fb_count = 0;
   uint32_t rd_t = 1;   // reader cursor: slot ...
   int rd_k = 0;        // ... and arrivals of that slot already handed out
-  int win = 0;         // lane i: n_t | B_t << 16 for slot win_t0 + i
-
-  uint64_t c_act = 0, c_done = 0, c_evict = 0, c_ovf = 0, c_sum_u = 0, c_sum_p = 0, c_sum_q = 0;
-  uint64_t c_dec_tok = 0, c_pf_tok = 0, c_useful = 0, c_stalled = 0, c_sum_lat = 0;
-  int c_max_lat = 0, c_max_u = 0, c_max_p = 0, c_max_q = 0;
+  int win = 0;         // lane i: n_t | B_t << 16 for the i-th slot of the current window
+  // statistics: lane k of (acc_hi:acc_lo) is counter SL_k; lanes 0..2 of mx are max U, |P|, |Q|
+  uint32_t acc_lo = 0, acc_hi = 0;
+  int mx = 0;
+  // per-lane partial sums over the requests whose completion this lane handled
+  uint32_t lat_lo = 0, lat_hi = 0, use_lo = 0, use_hi = 0;
+  int lat_max = 0;
   int trace_left = kp.trace_every, trace_idx = 0;
 
   auto fail = [&](int code, int t) {
@@ -173,31 +198,14 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   // n_t and B_t of slot t0 + lane (Section 2.1: n_t from a known law with mean lambda;
   // Theorem 2: B_t i.i.d. bounded integers with mean b)
   auto draw_slot = [&](uint32_t t0, int& n_out, int& b_out) {
+    const DLaw arr = laws[cellp.arrival];
+    const uint32_t* __restrict__ arr_thr = kp.blob + arr.off;
     uint32_t w0, w1, w2, w3;
     philox4x32_10(0u, t0 + static_cast<uint32_t>(lane), rep, 0u, kp.seed_lo, kp.seed_hi, w0, w1, w2, w3);
     int n = 0;
     for (int i = 0; i < arr.n; ++i) n += (w0 >= arr_thr[i]) ? 1 : 0;
     n_out = n;
     b_out = cellp.b_floor + ((w1 < cellp.b_frac_thr) ? 1 : 0);
-  };
-
-  // value = lo + #{thr <= u} by bisection inside the guide bucket of u
-  auto invert = [&](const DLaw& L, uint32_t u, bool on) -> int {
-    int lo = 0, hi = 0;
-    if (on && L.n > 0) {
-      const uint32_t* g = kp.blob + L.goff;
-      const uint32_t b = u >> 24;
-      lo = static_cast<int>(g[b]);
-      hi = static_cast<int>(g[b + 1]);
-    }
-    const uint32_t* th = kp.blob + L.off;
-    for (int it = 0; it < 34 && __any(lo < hi); ++it) {
-      if (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (th[mid] <= u) lo = mid + 1; else hi = mid;
-      }
-    }
-    return L.lo + lo;
   };
 
   // Generates the next block of never-activated requests, in arrival order, starting at
@@ -210,45 +218,63 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
       draw_slot(rd_t, n, b);
       if (rd_t + static_cast<uint32_t>(lane) > static_cast<uint32_t>(T)) n = 0;
       if (lane == 0) n -= rd_k;
-      const int incl = wave_incl_sum(n);
-      const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
+      const int incl = wave_incl_sum(n, lane);
+      const int total = rdl(incl, kWave - 1);
       const int excl = incl - n;
       if (total == 0) { rd_t += kWave; rd_k = 0; continue; }
       // expand: output lane i takes the slot s with excl[s] <= i < incl[s]
-      smem[SCR + lane] = 0;
+      smem[O_SCR + lane] = 0;
       wave_sync();
-      if (n > 0 && excl < kWave) smem[SCR + excl] = lane + 1;
+      if (n > 0 && excl < kWave) smem[O_SCR + excl] = lane + 1;
       wave_sync();
-      const int mark = smem[SCR + lane];
+      const int mark = smem[O_SCR + lane];
       wave_sync();
       const int cnt = min(total, kWave);
       const bool valid = lane < cnt;
-      const int owner = wave_incl_max(mark);
+      const int owner = wave_incl_max(mark, lane);
       const int src = valid ? owner - 1 : 0;
       const int ex_s = __shfl(excl, src, kWave);
       const int k = lane - ex_s + (src == 0 ? rd_k : 0);
       const uint32_t ta = rd_t + static_cast<uint32_t>(src);
       uint32_t w0, w1, w2, w3;
       philox4x32_10(static_cast<uint32_t>(k), ta, rep, 1u, kp.seed_lo, kp.seed_hi, w0, w1, w2, w3);
+      const uint32_t* __restrict__ class_thr = kp.blob + kp.class_off;
       int cls = 0;
       for (int i = 0; i + 1 < kp.n_classes; ++i) cls += (w0 >= class_thr[i]) ? 1 : 0;
       const DLaw pl = laws[kp.n_arrival_laws + cls];
       const DLaw dl = laws[kp.n_arrival_laws + kp.n_classes + cls];
-      fb_l = invert(pl, w1, valid);
-      fb_o = invert(dl, w2, valid);
+      // value = lo + #{thr <= u}: both laws bisected together inside the guide buckets of their words
+      int lo1 = 0, hi1 = 0, lo2 = 0, hi2 = 0;
+      if (valid) {
+        if (pl.n > 0) {
+          const uint32_t* g = kp.blob + pl.goff + (w1 >> (32 - kGuideBits));
+          lo1 = static_cast<int>(g[0]); hi1 = static_cast<int>(g[1]);
+        }
+        if (dl.n > 0) {
+          const uint32_t* g = kp.blob + dl.goff + (w2 >> (32 - kGuideBits));
+          lo2 = static_cast<int>(g[0]); hi2 = static_cast<int>(g[1]);
+        }
+      }
+      const uint32_t* th1 = kp.blob + pl.off;
+      const uint32_t* th2 = kp.blob + dl.off;
+      for (int it = 0; it < 34 && __any(lo1 < hi1 || lo2 < hi2); ++it) {
+        const bool a1 = lo1 < hi1, a2 = lo2 < hi2;
+        const int m1 = (lo1 + hi1) >> 1, m2 = (lo2 + hi2) >> 1;
+        const uint32_t v1 = a1 ? th1[m1] : 0u;
+        const uint32_t v2 = a2 ? th2[m2] : 0u;
+        if (a1) { if (v1 <= w1) lo1 = m1 + 1; else hi1 = m1; }
+        if (a2) { if (v2 <= w2) lo2 = m2 + 1; else hi2 = m2; }
+      }
+      fb_l = pl.lo + lo1;
+      fb_o = dl.lo + lo2;
       fb_t = static_cast<int>(ta);
       fb_count = cnt;
       if (total <= kWave) {
         rd_t += kWave;
         rd_k = 0;
       } else {
-        const int s63 = __builtin_amdgcn_readlane(src, kWave - 1);
-        rd_k = __builtin_amdgcn_readlane(k, kWave - 1) + 1;
-        rd_t += static_cast<uint32_t>(s63);
-      }
-      if (arr_rec && valid) {
-        const uint32_t id = fb_base + static_cast<uint32_t>(lane);
-        if (id < static_cast<uint32_t>(kp.max_requests)) arr_rec[id] = fb_t;
+        rd_k = rdl(k, kWave - 1) + 1;
+        rd_t += static_cast<uint32_t>(rdl(src, kWave - 1));
       }
     }
   };
@@ -256,354 +282,419 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   // Order-preserving removal of dead slots.
   auto compact = [&]() {
     int out = 0, new_pf = -1;
-    for (int base = 0; base < n_slots; base += kWave) {
-      const int pos = base + lane;
-      const bool in = pos < n_slots;
-      int f[F_NFIELDS];
-#pragma unroll
-      for (int q = 0; q < F_NFIELDS; ++q) f[q] = in ? a_get(q, pos) : 0;
-      const bool live = in && (f[F_REM] > 0 || f[F_PLEFT] > 0);
-      const uint64_t m = __ballot(live);
-      const int dst = out + lanes_below(m);
-      const uint64_t pm = __ballot(live && f[F_PLEFT] > 0);
-      if (pm != 0 && new_pf < 0) {
-        const int first = __builtin_ctzll(pm);
-        new_pf = out + __popcll(m & ((1ull << first) - 1ull));
+    if (n_slots <= LC) {
+      for (int base = 0; base < n_slots; base += kWave) {
+        const int pos = base + lane;
+        const int rem = smem[pos], pl = smem[O_PL + pos];
+        const v4i rec = *reinterpret_cast<const v4i*>(&smem[O_REC + 4 * pos]);
+        const bool live = pos < n_slots && (rem > 0 || pl > 0);
+        const uint64_t m = __ballot(live);
+        const uint64_t pm = __ballot(live && pl > 0);
+        const int dst = out + lanes_below(m);
+        if (pm != 0 && new_pf < 0) new_pf = out + __popcll(m & ((1ull << __builtin_ctzll(pm)) - 1ull));
+        wave_sync();
+        if (live) {
+          smem[dst] = rem;
+          smem[O_PL + dst] = pl;
+          *reinterpret_cast<v4i*>(&smem[O_REC + 4 * dst]) = rec;
+        }
+        wave_sync();
+        out += __popcll(m);
       }
-      if (live) {
-#pragma unroll
-        for (int q = 0; q < F_NFIELDS; ++q) a_set(q, dst, f[q]);
+      for (int base = out; base < n_slots; base += kWave) {
+        const int pos = base + lane;
+        if (pos < n_slots) { smem[pos] = -1; smem[O_PL + pos] = 0; }
       }
-      wave_sync();
-      out += __popcll(m);
-    }
-    for (int base = out; base < n_slots; base += kWave) {
-      const int pos = base + lane;
-      if (pos < n_slots) { a_set(F_REM, pos, -1); a_set(F_PLEFT, pos, 0); }
+    } else {
+      for (int base = 0; base < n_slots; base += kWave) {
+        const int pos = base + lane;
+        const bool in = pos < n_slots;
+        int rem = -1, pl = 0;
+        v4i rec = {0, 0, 0, 0};
+        if (in) {
+          if (base < LC) {
+            rem = smem[pos]; pl = smem[O_PL + pos];
+            rec = *reinterpret_cast<const v4i*>(&smem[O_REC + 4 * pos]);
+          } else {
+            rem = hREM[pos - LC]; pl = hPL[pos - LC];
+            rec = *reinterpret_cast<const v4i*>(&hREC[4 * static_cast<size_t>(pos - LC)]);
+          }
+        }
+        const bool live = in && (rem > 0 || pl > 0);
+        const uint64_t m = __ballot(live);
+        const uint64_t pm = __ballot(live && pl > 0);
+        const int dst = out + lanes_below(m);
+        if (pm != 0 && new_pf < 0) new_pf = out + __popcll(m & ((1ull << __builtin_ctzll(pm)) - 1ull));
+        wave_sync();
+        if (live) slot_store(dst, rem, pl, rec);
+        wave_sync();
+        out += __popcll(m);
+      }
+      for (int base = out; base < n_slots; base += kWave) {
+        const int pos = base + lane;
+        if (pos < n_slots) rem_pl_store(pos, -1, 0);
+      }
     }
     wave_sync();
     n_slots = out;
     pf_first = new_pf < 0 ? n_slots : new_pf;
   };
 
-  // Moves the head of Q into P (Algorithm 2: pick by FIFO, activate).
-  auto admit_head = [&](int t) {
-    int id, l, o, ta;
-    if (sdepth > 0) {
-      const int d = sdepth - 1;
-      id = rfl(s_get(S_ID, d)); l = rfl(s_get(S_L, d)); o = rfl(s_get(S_O, d)); ta = rfl(s_get(S_TARR, d));
-      sdepth = d;
-    } else {
-      if (static_cast<int>(fresh_next - fb_base) >= fb_count) refill_block();
-      const int idx = static_cast<int>(fresh_next - fb_base);
-      if (idx >= fb_count) { fail(FCS_ESTATE, t); return; }
-      id = static_cast<int>(fresh_next);
-      l = __builtin_amdgcn_readlane(fb_l, idx);
-      o = __builtin_amdgcn_readlane(fb_o, idx);
-      ta = __builtin_amdgcn_readlane(fb_t, idx);
-      fresh_next += 1u;
-    }
-    if (n_slots == CAP) {
-      if (n_live < n_slots) compact();
-      if (n_slots == CAP) { fail(FCS_EOVERFLOW, t); return; }
-    }
-    const int pos = n_slots;
-    if (lane == 0) {
-      a_set(F_REM, pos, -1); a_set(F_PLEFT, pos, l); a_set(F_L, pos, l);
-      a_set(F_O, pos, o); a_set(F_TARR, pos, ta); a_set(F_ID, pos, id);
-    }
-    wave_sync();
-    n_slots = pos + 1;
-    if (n_pf == 0 || pf_first > pos) pf_first = pos;
-    U += l;
-    n_live += 1;
-    n_pf += 1;
-    c_act += 1;
-  };
-
-  auto head_prompt = [&](int t) -> int {
-    if (sdepth > 0) return rfl(s_get(S_L, sdepth - 1));
-    if (static_cast<int>(fresh_next - fb_base) >= fb_count) refill_block();
-    const int idx = static_cast<int>(fresh_next - fb_base);
-    if (idx >= fb_count) { fail(FCS_ESTATE, t); return M; }
-    return __builtin_amdgcn_readlane(fb_l, idx);
-  };
-
-  // Evicts the most recently activated request (Section 3.3: last in, first out).
+  // Evicts the most recently activated request (Section 3.3: last in, first out); it loses
+  // its progress and goes back to the front of Q.
   auto evict_newest = [&](int t) {
     int pos = n_slots - 1;
     int rem = 0, pleft = 0;
     for (; pos >= 0; --pos) {
-      rem = rfl(a_get(F_REM, pos));
-      pleft = rfl(a_get(F_PLEFT, pos));
+      rem_pl_load(pos, rem, pleft);
+      rem = rfl(rem);
+      pleft = rfl(pleft);
       if (rem > 0 || pleft > 0) break;
     }
     if (pos < 0) { fail(FCS_ESTATE, t); return; }
-    const int l = rfl(a_get(F_L, pos)), o = rfl(a_get(F_O, pos));
-    const int ta = rfl(a_get(F_TARR, pos)), id = rfl(a_get(F_ID, pos));
+    const v4i rec = rec_load(pos);
+    const int l = rfl(rec.x), o = rfl(rec.y);
     if (pleft > 0) { U -= l; n_pf -= 1; }
     else { U -= l + (o - rem); n_dec -= 1; }
     n_live -= 1;
-    c_evict += 1;
     if (sdepth == SCAP) { fail(FCS_EOVERFLOW, t); return; }
     if (lane == 0) {
-      s_set(S_ID, sdepth, id); s_set(S_L, sdepth, l); s_set(S_O, sdepth, o); s_set(S_TARR, sdepth, ta);
-      a_set(F_REM, pos, -1);
-      a_set(F_PLEFT, pos, 0);
+      if (sdepth < kStackLds) *reinterpret_cast<v4i*>(&smem[O_STK + 4 * sdepth]) = rec;
+      else *reinterpret_cast<v4i*>(&hSTK[4 * static_cast<size_t>(sdepth - kStackLds)]) = rec;
+      rem_pl_store(pos, -1, 0);
     }
     wave_sync();
     sdepth += 1;
     n_slots = pos;
     if (pf_first > n_slots) pf_first = n_slots;
+    head_l = l;
   };
 
-  // per-slot accumulators of completions (released after U_t is measured: Section 2.1)
-  int rel_sum = 0, n_done = 0;
-  auto complete_at = [&](int pos, int t) {
-    const int l = rfl(a_get(F_L, pos)), o = rfl(a_get(F_O, pos));
-    const int ta = rfl(a_get(F_TARR, pos)), id = rfl(a_get(F_ID, pos));
-    const int lat = t - ta + 1;
-    rel_sum += l + o;
-    n_done += 1;
-    c_sum_lat += static_cast<uint64_t>(lat);
-    c_max_lat = max(c_max_lat, lat);
-    c_useful += static_cast<uint64_t>(o);
-    if (lane == 0) {
-      a_set(F_REM, pos, -1);
-      if (hist) atomicAdd(&hist[min(lat >> kp.hist_shift, kp.hist_bins - 1)], 1u);
-      if (comp_rec && id < kp.max_requests) comp_rec[id] = t;
-    }
-    wave_sync();
-  };
-
-  // =============================== slots 1..T ====================================
+  // =============================== slots 1..T ========================================
   for (int t = 1; t <= T && !err; ++t) {
-    // ---- 1. arrivals -------------------------------------------------------------
+    int x = 0;  // this slot's contribution to the statistics, one counter per lane
+
+    // ---- 1. arrivals ---------------------------------------------------------------
     const int wi = (t - 1) & (kWave - 1);
     if (wi == 0) {
       int n, b;
       draw_slot(static_cast<uint32_t>(t), n, b);
       win = n | (b << 16);
-    }
-    const int nb = __builtin_amdgcn_readlane(win, wi);
-    const int n_t = nb & 0xffff, B_t = nb >> 16;
-    arrived += static_cast<uint32_t>(n_t);
-    if (arrived >= 0x7fffff00u) fail(FCS_EOVERFLOW, t);
-
-    // ---- 2. admission ------------------------------------------------------------
-    int qlen = sdepth + static_cast<int>(arrived - fresh_next);
-    if (!greedy) {
-      int k = min(B_t, qlen);
-      for (; k > 0 && !err; --k) admit_head(t);
-    } else {
-      while (qlen > 0 && !err) {
-        const int lh = head_prompt(t);
-        if (U + n_live + lh + 1 > M) break;
-        admit_head(t);
-        qlen -= 1;
+      if (arrived >= 0x7ffe0000u) fail(FCS_EOVERFLOW, t);
+      if (arr_rec) {  // arrival slots of the requests of this window, by arrival id
+        const int tt = t + lane;
+        const int ne = tt <= T ? n : 0;
+        const int excl = wave_incl_sum(ne, lane) - ne;
+        for (int k = 0; k < ne; ++k) {
+          const uint32_t id = arrived + static_cast<uint32_t>(excl + k);
+          if (id < static_cast<uint32_t>(kp.max_requests)) arr_rec[id] = tt;
+        }
       }
     }
+    const int nb = rdl(win, wi);
+    const int B_t = nb >> 16;
+    arrived += static_cast<uint32_t>(nb & 0xffff);
 
-    // ---- 3. overflow ---------------------------------------------------------------
+    // ---- 2. admission: FLOW moves min(B_t, |Q|) head requests, GREEDY while the head fits ----
+    {
+      int qlen = sdepth + static_cast<int>(arrived - fresh_next);
+      int room = greedy ? qlen : min(B_t, qlen);
+      int admitted = 0;
+      while (room > 0 && !err) {
+        const bool from_stack = sdepth > 0;
+        int idx = 0;
+        if (!from_stack) {
+          if (static_cast<int>(fresh_next - fb_base) >= fb_count) refill_block();
+          idx = static_cast<int>(fresh_next - fb_base);
+          if (idx >= fb_count) { fail(FCS_ESTATE, t); break; }
+        }
+        if (greedy) {
+          if (head_l < 0) {
+            if (from_stack) {
+              const int d = sdepth - 1;
+              head_l = rfl(d < kStackLds ? smem[O_STK + 4 * d] : hSTK[4 * static_cast<size_t>(d - kStackLds)]);
+            } else {
+              head_l = rdl(fb_l, idx);
+            }
+          }
+          if (U + n_live + head_l + 1 > M) break;
+        }
+        if (n_slots == CAP) {
+          if (n_live < n_slots) compact();
+          if (n_slots == CAP) { fail(FCS_EOVERFLOW, t); break; }
+        }
+        const int pos = n_slots;
+        int l;
+        if (from_stack) {
+          const int d = sdepth - 1;
+          v4i rec;
+          if (d < kStackLds) rec = *reinterpret_cast<const v4i*>(&smem[O_STK + 4 * d]);
+          else rec = *reinterpret_cast<const v4i*>(&hSTK[4 * static_cast<size_t>(d - kStackLds)]);
+          l = rfl(rec.x);
+          if (lane == 0) slot_store(pos, -1, l, rec);
+          sdepth = d;
+        } else {
+          l = rdl(fb_l, idx);
+          if (lane == idx) {
+            const v4i rec = {fb_l, fb_o, fb_t, static_cast<int>(fresh_next)};
+            slot_store(pos, -1, fb_l, rec);
+          }
+          fresh_next += 1u;
+        }
+        wave_sync();
+        n_slots = pos + 1;
+        if (n_pf == 0 || pf_first > pos) pf_first = pos;
+        U += l;
+        n_live += 1;
+        n_pf += 1;
+        admitted += 1;
+        room -= 1;
+        head_l = -1;
+      }
+      if (admitted) x = wrl(admitted, SL_ACT, x);
+    }
+
+    // ---- 3. overflow: evict newest while the provisioned usage exceeds M --------------------
     if (U + n_live > M) {
-      c_ovf += 1;
-      do { evict_newest(t); } while (U + n_live > M && !err);
+      int ev = 0;
+      do { evict_newest(t); ev += 1; } while (U + n_live > M && !err);
+      x = wrl(ev, SL_EVICT, x);
+      x = wrl(1, SL_OVF, x);
     }
     if (err) break;
-    qlen = sdepth + static_cast<int>(arrived - fresh_next);
+    const int qlen = sdepth + static_cast<int>(arrived - fresh_next);
 
-    // ---- 4a. chunked prefill under the token budget, activation order ---------------
+    // ---- 4a. chunked prefill under the token budget, activation order -----------------------
     int budget = kp.tau;
     int new_dec = 0;
     if (n_pf > 0) {
       int todo = n_pf;
-      int base = pf_first;
+      int base = pf_first & ~(kWave - 1);
       int first_left = -1;
+      const int budget0 = budget;
       while (todo > 0 && budget > 0 && base < n_slots) {
         const int pos = base + lane;
-        const int pl = pos < n_slots ? a_get(F_PLEFT, pos) : 0;
+        int pl, ov;
+        if (base < LC) { pl = smem[O_PL + pos]; ov = smem[O_REC + 4 * pos + 1]; }
+        else if (pos < n_slots) { pl = hPL[pos - LC]; ov = hREC[4 * static_cast<size_t>(pos - LC) + 1]; }
+        else { pl = 0; ov = 0; }
         uint64_t m = __ballot(pl > 0);
-        int last_i = kWave - 1;
         while (m != 0 && budget > 0) {
           const int i = __builtin_ctzll(m);
           m &= m - 1;
           const int p = base + i;
-          int left = __builtin_amdgcn_readlane(pl, i);
+          int left = rdl(pl, i);
           const int d = min(min(kp.chunk, left), budget);
           left -= d;
           budget -= d;
-          c_pf_tok += static_cast<uint64_t>(d);
           todo -= 1;
           if (left == 0) {
-            // the chunk that ends the prompt yields token 1: enter decode with j = 0 here,
-            // the decode pass of this slot makes it j = 1
-            const int o = rfl(a_get(F_O, p));
-            if (lane == 0) { a_set(F_PLEFT, p, 0); a_set(F_REM, p, o); }
-            wave_sync();
+            // the chunk that ends the prompt yields token 1: the entry becomes o here and the
+            // decode pass of this slot makes it o - 1
+            const int o = rdl(ov, i);
+            if (lane == 0) rem_pl_store(p, o, 0);
             new_dec += 1;
           } else {
-            if (lane == 0) a_set(F_PLEFT, p, left);
-            wave_sync();
+            if (lane == 0) {
+              if (p < LC) smem[O_PL + p] = left; else hPL[p - LC] = left;
+            }
             if (first_left < 0) first_left = p;
           }
-          last_i = i;
         }
+        wave_sync();
         if (m != 0) {  // budget ran out inside this chunk
           if (first_left < 0) first_left = base + __builtin_ctzll(m);
           break;
         }
-        (void)last_i;
         base += kWave;
       }
       if (first_left >= 0) pf_first = first_left;
       else pf_first = (todo > 0) ? min(base, n_slots) : n_slots;
       n_pf -= new_dec;
+      x = wrl(budget0 - budget, SL_PF_TOK, x);
     }
 
-    // ---- 4b. decode growth: one token per decoding request while budget lasts --------
-    rel_sum = 0;
-    n_done = 0;
-    int advanced;  // old decoders that got a token
+    // ---- 4b. decode growth: one token per decoding request while budget lasts ----------------
+    int rel_sum = 0, n_done = 0;  // completions of this slot: released footprint and count
+    // called where lanes flagged `mine` own a request (slot `pos`) that generated its last token
+    auto complete = [&](bool mine, int pos) {
+      const uint64_t m0 = __ballot(mine);
+      if (m0 == 0) return;
+      int relv = 0;
+      if (mine) {
+        v4i rec;
+        if (pos < LC) rec = *reinterpret_cast<const v4i*>(&smem[O_REC + 4 * pos]);
+        else rec = *reinterpret_cast<const v4i*>(&hREC[4 * static_cast<size_t>(pos - LC)]);
+        relv = rec.x + rec.y;                       // l + o, released at the end of the slot
+        const int lat = t - rec.z + 1;              // arrival to completion, both slots counted
+        const uint32_t s = lat_lo + static_cast<uint32_t>(lat);
+        lat_hi += (s < lat_lo) ? 1u : 0u;
+        lat_lo = s;
+        const uint32_t u = use_lo + static_cast<uint32_t>(rec.y);
+        use_hi += (u < use_lo) ? 1u : 0u;
+        use_lo = u;
+        lat_max = max(lat_max, lat);
+        if (hist) atomicAdd(&hist[min(lat >> kp.hist_shift, kp.hist_bins - 1)], 1u);
+        if (comp_rec && rec.w < kp.max_requests) comp_rec[rec.w] = t;
+      }
+      uint64_t m = m0;
+      n_done += __popcll(m);
+      do {
+        rel_sum += rdl(relv, __builtin_ctzll(m));
+        m &= m - 1;
+      } while (m != 0);
+    };
+
+    int advanced;  // requests already decoding that got a token
     if (budget >= n_dec) {
       advanced = n_dec;
       const int lim = min(n_slots, LC);
       for (int b0 = 0; b0 < lim; b0 += kLdsBlock) {
         const int p0 = b0 + (lane << 2);
-        v4i v = *reinterpret_cast<v4i*>(&smem[F_REM * LC + p0]);
+        v4i v = *reinterpret_cast<const v4i*>(&smem[p0]);
         v -= 1;
-        *reinterpret_cast<v4i*>(&smem[F_REM * LC + p0]) = v;
-        wave_sync();
-        const uint32_t mn = min(min(static_cast<uint32_t>(v.x), static_cast<uint32_t>(v.y)),
-                                min(static_cast<uint32_t>(v.z), static_cast<uint32_t>(v.w)));
-        if (__ballot(mn == 0u) != 0) {
+        if (__ballot(umin4(v) == 0u) != 0) {
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
-            uint64_t m = __ballot(v[c] == 0);
-            while (m != 0) {
-              const int i = __builtin_ctzll(m);
-              m &= m - 1;
-              complete_at(b0 + (i << 2) + c, t);
-            }
+            const bool d = v[c] == 0;
+            complete(d, p0 + c);
+            if (d) v[c] = -1;
           }
         }
+        *reinterpret_cast<v4i*>(&smem[p0]) = v;
+        wave_sync();
       }
       for (int base = LC; base < n_slots; base += kWave) {
         const int pos = base + lane;
         const bool in = pos < n_slots;
-        int v = in ? hA[static_cast<size_t>(F_REM) * HC + (pos - LC)] : -1;
+        int v = in ? hREM[pos - LC] : -1;
         v -= 1;
-        if (in) hA[static_cast<size_t>(F_REM) * HC + (pos - LC)] = v;
+        const bool d = in && v == 0;
+        complete(d, pos);
+        if (in) hREM[pos - LC] = d ? -1 : v;
         wave_sync();
-        uint64_t m = __ballot(in && v == 0);
-        while (m != 0) {
-          const int i = __builtin_ctzll(m);
-          m &= m - 1;
-          complete_at(base + i, t);
-        }
       }
     } else {
-      // budget binds: the first `budget` old decoders in activation order advance; requests
-      // that finished their prompt in this slot (rem == o) take their first token for free
+      // budget binds: the first `budget` already-decoding requests in activation order advance;
+      // requests that finished their prompt in this slot (entry == o) take token 1 for free
       int left = budget;
       advanced = 0;
       for (int base = 0; base < n_slots; base += kWave) {
         const int pos = base + lane;
         const bool in = pos < n_slots;
-        int v = in ? a_get(F_REM, pos) : -1;
+        int v = -1, ov = 0;
+        if (in) {
+          if (base < LC) { v = smem[pos]; ov = smem[O_REC + 4 * pos + 1]; }
+          else { v = hREM[pos - LC]; ov = hREC[4 * static_cast<size_t>(pos - LC) + 1]; }
+        }
         const bool dec = v > 0;
-        const bool fresh = dec && new_dec > 0 && v == a_get(F_O, pos);
+        const bool fresh = dec && new_dec > 0 && v == ov;
         const bool old = dec && !fresh;
         const uint64_t om = __ballot(old);
         const bool go = fresh || (old && lanes_below(om) < left);
         const int took = min(__popcll(om), left);
         left -= took;
         advanced += took;
-        if (go) { v -= 1; a_set(F_REM, pos, v); }
-        wave_sync();
-        uint64_t m = __ballot(go && v == 0);
-        while (m != 0) {
-          const int i = __builtin_ctzll(m);
-          m &= m - 1;
-          complete_at(base + i, t);
+        if (go) v -= 1;
+        const bool d = go && v == 0;
+        complete(d, pos);
+        if (go) {
+          if (base < LC) smem[pos] = d ? -1 : v; else hREM[pos - LC] = d ? -1 : v;
         }
+        wave_sync();
       }
-      c_stalled += static_cast<uint64_t>(n_dec - advanced);
+      x = wrl(n_dec - advanced, SL_STALLED, x);
     }
-    c_dec_tok += static_cast<uint64_t>(advanced + new_dec);
-    U += advanced + new_dec;
+    const int tokens = advanced + new_dec;
+    U += tokens;
     n_dec += new_dec;
 
-    // ---- 5. measure -------------------------------------------------------------------
-    c_sum_u += static_cast<uint64_t>(U);
-    c_sum_p += static_cast<uint64_t>(n_live);
-    c_sum_q += static_cast<uint64_t>(qlen);
-    c_max_u = max(c_max_u, U);
-    c_max_p = max(c_max_p, n_live);
-    c_max_q = max(c_max_q, qlen);
+    // ---- 5. measure (Section 2.1: U_t after processing, before completed requests leave) --------
+    x = wrl(U, SL_SUM_U, x);
+    x = wrl(n_live, SL_SUM_P, x);
+    x = wrl(qlen, SL_SUM_Q, x);
+    x = wrl(tokens, SL_DEC_TOK, x);
+    if (n_done) x = wrl(n_done, SL_DONE, x);
+    {
+      const uint32_t s = acc_lo + static_cast<uint32_t>(x);
+      acc_hi += (s < acc_lo) ? 1u : 0u;
+      acc_lo = s;
+      mx = max(mx, x);
+    }
     if (kp.trace_every > 0 && --trace_left == 0) {
       trace_left = kp.trace_every;
       if (lane == 0) {
-        if (trq) trq[trace_idx] = qlen;
-        if (tru) tru[trace_idx] = U;
+        if (kp.out.trace_q) kp.out.trace_q[static_cast<size_t>(path) * kp.n_trace + trace_idx] = qlen;
+        if (kp.out.trace_u) kp.out.trace_u[static_cast<size_t>(path) * kp.n_trace + trace_idx] = U;
       }
       trace_idx += 1;
     }
 
-    // ---- 6. complete: release the footprint at the end of the slot -----------------------
+    // ---- 6. complete: the footprint is released at the end of the slot -------------------------
     U -= rel_sum;
     n_live -= n_done;
     n_dec -= n_done;
-    c_done += static_cast<uint64_t>(n_done);
     if (n_slots - n_live >= kCompactSlack) compact();
   }
 
-  // ---- epilogue: arrival records of requests never activated, digest, counters ----------
-  if (!err && arr_rec) {
-    uint32_t keep = fresh_next;
-    int guard = 0;
-    while (fb_base + static_cast<uint32_t>(fb_count) < arrived && guard++ < (1 << 24)) {
-      fresh_next = fb_base + static_cast<uint32_t>(fb_count);
-      if (fresh_next >= static_cast<uint32_t>(kp.max_requests)) break;
-      refill_block();
-      if (fb_count == 0) break;
-    }
-    fresh_next = keep;
-  }
+  // ---- epilogue: digest of the final state, counters --------------------------------------------
   uint64_t h = 14695981039346656037ull;
-  auto mix = [&](uint64_t x) { h = (h ^ x) * 1099511628211ull; };
+  auto mix = [&](uint64_t w) { h = (h ^ w) * 1099511628211ull; };
   if (!err) {
     compact();
     mix(static_cast<uint64_t>(n_slots));
     for (int pos = 0; pos < n_slots; ++pos) {
-      const int rem = rfl(a_get(F_REM, pos)), pleft = rfl(a_get(F_PLEFT, pos));
-      const int l = rfl(a_get(F_L, pos)), o = rfl(a_get(F_O, pos)), id = rfl(a_get(F_ID, pos));
+      int rem, pleft;
+      rem_pl_load(pos, rem, pleft);
+      rem = rfl(rem);
+      pleft = rfl(pleft);
+      const v4i rec = rec_load(pos);
+      const int l = rfl(rec.x), o = rfl(rec.y), id = rfl(rec.w);
       mix(static_cast<uint64_t>(id));
       mix(static_cast<uint64_t>(rem > 0 ? o - rem : 0));
       mix(static_cast<uint64_t>(l - pleft));
     }
     mix(static_cast<uint64_t>(sdepth));
-    for (int d = sdepth - 1; d >= 0; --d) mix(static_cast<uint64_t>(rfl(s_get(S_ID, d))));
+    for (int d = sdepth - 1; d >= 0; --d) {
+      const int id = rfl(d < kStackLds ? smem[O_STK + 4 * d + 3] : hSTK[4 * static_cast<size_t>(d - kStackLds) + 3]);
+      mix(static_cast<uint64_t>(id));
+    }
     mix(static_cast<uint64_t>(arrived - fresh_next));
   }
+  // reduce the per-lane completion sums over the wavefront
+  uint64_t lat_sum = (static_cast<uint64_t>(lat_hi) << 32) | lat_lo;
+  uint64_t use_sum = (static_cast<uint64_t>(use_hi) << 32) | use_lo;
+#pragma unroll
+  for (int d = kWave / 2; d > 0; d >>= 1) {
+    lat_sum += __shfl_xor(lat_sum, d, kWave);
+    use_sum += __shfl_xor(use_sum, d, kWave);
+    lat_max = max(lat_max, __shfl_xor(lat_max, d, kWave));
+  }
+  uint64_t* C = kp.out.counters + static_cast<size_t>(path) * FCS_N_COUNTERS;
+  const uint64_t acc = (static_cast<uint64_t>(acc_hi) << 32) | acc_lo;
+  int slot = -1;
+  switch (lane) {
+    case SL_SUM_U: slot = FCS_C_SUM_U; break;
+    case SL_SUM_P: slot = FCS_C_SUM_P; break;
+    case SL_SUM_Q: slot = FCS_C_SUM_Q; break;
+    case SL_DEC_TOK: slot = FCS_C_DECODE_TOKENS; break;
+    case SL_ACT: slot = FCS_C_ACTIVATIONS; break;
+    case SL_DONE: slot = FCS_C_COMPLETED; break;
+    case SL_EVICT: slot = FCS_C_EVICTIONS; break;
+    case SL_OVF: slot = FCS_C_OVERFLOW_STEPS; break;
+    case SL_PF_TOK: slot = FCS_C_PREFILL_TOKENS; break;
+    case SL_STALLED: slot = FCS_C_STALLED; break;
+    default: break;
+  }
+  if (slot >= 0) C[slot] = acc;
+  if (lane == SL_SUM_U) C[FCS_C_MAX_U] = static_cast<uint64_t>(mx);
+  if (lane == SL_SUM_P) C[FCS_C_MAX_P] = static_cast<uint64_t>(mx);
+  if (lane == SL_SUM_Q) C[FCS_C_MAX_Q] = static_cast<uint64_t>(mx);
   if (lane == 0) {
-    uint64_t* C = kp.out.counters + static_cast<size_t>(path) * FCS_N_COUNTERS;
     C[FCS_C_ARRIVED] = arrived;
-    C[FCS_C_ACTIVATIONS] = c_act;
-    C[FCS_C_COMPLETED] = c_done;
-    C[FCS_C_EVICTIONS] = c_evict;
-    C[FCS_C_OVERFLOW_STEPS] = c_ovf;
-    C[FCS_C_SUM_U] = c_sum_u;
-    C[FCS_C_SUM_P] = c_sum_p;
-    C[FCS_C_SUM_Q] = c_sum_q;
-    C[FCS_C_DECODE_TOKENS] = c_dec_tok;
-    C[FCS_C_PREFILL_TOKENS] = c_pf_tok;
-    C[FCS_C_USEFUL_TOKENS] = c_useful;
-    C[FCS_C_STALLED] = c_stalled;
-    C[FCS_C_SUM_LATENCY] = c_sum_lat;
-    C[FCS_C_MAX_LATENCY] = static_cast<uint64_t>(c_max_lat);
-    C[FCS_C_MAX_U] = static_cast<uint64_t>(c_max_u);
-    C[FCS_C_MAX_P] = static_cast<uint64_t>(c_max_p);
-    C[FCS_C_MAX_Q] = static_cast<uint64_t>(c_max_q);
+    C[FCS_C_USEFUL_TOKENS] = use_sum;
+    C[FCS_C_SUM_LATENCY] = lat_sum;
+    C[FCS_C_MAX_LATENCY] = static_cast<uint64_t>(lat_max);
     C[FCS_C_FINAL_U] = static_cast<uint64_t>(U);
     C[FCS_C_FINAL_P] = static_cast<uint64_t>(n_live);
     C[FCS_C_FINAL_Q] = static_cast<uint64_t>(sdepth) + static_cast<uint64_t>(arrived - fresh_next);
