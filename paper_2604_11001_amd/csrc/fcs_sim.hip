@@ -92,6 +92,17 @@ __device__ __forceinline__ int lanes_below(uint64_t mask) {
                                    __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
 }
 
+#define LIKELY(c) __builtin_expect(!!(c), 1)
+#define UNLIKELY(c) __builtin_expect(!!(c), 0)
+
+// 16-byte LDS / global accesses of four consecutive words (addresses are multiples of four words)
+__device__ __forceinline__ v4i ld4(const int32_t* p) {
+  return *reinterpret_cast<const v4i*>(__builtin_assume_aligned(p, 16));
+}
+__device__ __forceinline__ void st4(int32_t* p, v4i v) {
+  *reinterpret_cast<v4i*>(__builtin_assume_aligned(p, 16)) = v;
+}
+
 __device__ __forceinline__ uint32_t umin4(v4i v) {
   return min(min(static_cast<uint32_t>(v.x), static_cast<uint32_t>(v.y)),
              min(static_cast<uint32_t>(v.z), static_cast<uint32_t>(v.w)));
@@ -102,7 +113,7 @@ enum { SL_SUM_U = 0, SL_SUM_P, SL_SUM_Q, SL_DEC_TOK, SL_ACT, SL_DONE, SL_EVICT, 
        SL_STALLED, SL_COUNT };
 
 __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
-  extern __shared__ int32_t smem[];
+  extern __shared__ __attribute__((aligned(16))) int32_t smem[];
   const int lane = static_cast<int>(threadIdx.x);
   const int path = static_cast<int>(blockIdx.x);
   if (path >= kp.n_paths) return;
@@ -119,34 +130,34 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   // LDS word offsets
   const int O_PL = LC, O_REC = 2 * LC, O_STK = F_NFIELDS * LC, O_SCR = O_STK + S_NFIELDS * kStackLds;
   // spill region of this path
-  int32_t* __restrict__ hREM = kp.spill + static_cast<size_t>(path) * kp.spill_stride;
-  int32_t* __restrict__ hPL = hREM + HC;
-  int32_t* __restrict__ hREC = hPL + HC;
-  int32_t* __restrict__ hSTK = hREM + static_cast<size_t>(F_NFIELDS) * HC;
+  int32_t* const hREM = kp.spill + static_cast<size_t>(path) * kp.spill_stride;
+#define hPL (hREM + HC)
+#define hREC (hREM + 2 * static_cast<size_t>(HC))
+#define hSTK (hREM + static_cast<size_t>(F_NFIELDS) * HC)
 
   // ---- record accessors (uniform position: every lane reads the same record) ---------
   auto rec_load = [&](int pos) -> v4i {
-    if (pos < LC) return *reinterpret_cast<const v4i*>(&smem[O_REC + 4 * pos]);
-    return *reinterpret_cast<const v4i*>(&hREC[4 * static_cast<size_t>(pos - LC)]);
+    if (pos < LC) return ld4(&smem[O_REC + 4 * pos]);
+    return ld4(&hREC[4 * static_cast<size_t>(pos - LC)]);
   };
   auto slot_store = [&](int pos, int rem, int pleft, v4i rec) {  // executed by one lane
-    if (pos < LC) {
+    if (LIKELY(pos < LC)) {
       smem[pos] = rem;
       smem[O_PL + pos] = pleft;
-      *reinterpret_cast<v4i*>(&smem[O_REC + 4 * pos]) = rec;
+      st4(&smem[O_REC + 4 * pos], rec);
     } else {
       const size_t q = static_cast<size_t>(pos - LC);
       hREM[q] = rem;
       hPL[q] = pleft;
-      *reinterpret_cast<v4i*>(&hREC[4 * q]) = rec;
+      st4(&hREC[4 * q], rec);
     }
   };
   auto rem_pl_load = [&](int pos, int& rem, int& pl) {
-    if (pos < LC) { rem = smem[pos]; pl = smem[O_PL + pos]; }
+    if (LIKELY(pos < LC)) { rem = smem[pos]; pl = smem[O_PL + pos]; }
     else { rem = hREM[pos - LC]; pl = hPL[pos - LC]; }
   };
   auto rem_pl_store = [&](int pos, int rem, int pl) {
-    if (pos < LC) { smem[pos] = rem; smem[O_PL + pos] = pl; }
+    if (LIKELY(pos < LC)) { smem[pos] = rem; smem[O_PL + pos] = pl; }
     else { hREM[pos - LC] = rem; hPL[pos - LC] = pl; }
   };
 
@@ -164,6 +175,11 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
     smem[O_PL + i] = 0;
   }
   wave_sync();
+  // the completion handler runs in the lanes that own the finished slots: keep what it needs in
+  // vector registers so that it costs no scalar registers in the main loop
+  uint64_t hist_v = reinterpret_cast<uint64_t>(hist), comp_v = reinterpret_cast<uint64_t>(comp_rec);
+  int hist_last_v = kp.hist_bins - 1, hist_shift_v = kp.hist_shift, max_req_v = kp.max_requests;
+  asm volatile("" : "+v"(hist_v), "+v"(comp_v), "+v"(hist_last_v), "+v"(hist_shift_v), "+v"(max_req_v));
 
   // ---- state (wave-uniform) ------------------------------------------------------------
   int U = 0;           // sum over P of (l + j)
@@ -189,7 +205,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   // per-lane partial sums over the requests whose completion this lane handled
   uint32_t lat_lo = 0, lat_hi = 0, use_lo = 0, use_hi = 0;
   int lat_max = 0;
-  int trace_left = kp.trace_every, trace_idx = 0;
+  int trace_left = kp.trace_every > 0 ? kp.trace_every : 0x7fffffff, trace_idx = 0;  // T < 2^30
 
   auto fail = [&](int code, int t) {
     if (!err) { err = code; err_step = t; }
@@ -286,7 +302,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
       for (int base = 0; base < n_slots; base += kWave) {
         const int pos = base + lane;
         const int rem = smem[pos], pl = smem[O_PL + pos];
-        const v4i rec = *reinterpret_cast<const v4i*>(&smem[O_REC + 4 * pos]);
+        const v4i rec = ld4(&smem[O_REC + 4 * pos]);
         const bool live = pos < n_slots && (rem > 0 || pl > 0);
         const uint64_t m = __ballot(live);
         const uint64_t pm = __ballot(live && pl > 0);
@@ -296,7 +312,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
         if (live) {
           smem[dst] = rem;
           smem[O_PL + dst] = pl;
-          *reinterpret_cast<v4i*>(&smem[O_REC + 4 * dst]) = rec;
+          st4(&smem[O_REC + 4 * dst], rec);
         }
         wave_sync();
         out += __popcll(m);
@@ -314,10 +330,10 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
         if (in) {
           if (base < LC) {
             rem = smem[pos]; pl = smem[O_PL + pos];
-            rec = *reinterpret_cast<const v4i*>(&smem[O_REC + 4 * pos]);
+            rec = ld4(&smem[O_REC + 4 * pos]);
           } else {
             rem = hREM[pos - LC]; pl = hPL[pos - LC];
-            rec = *reinterpret_cast<const v4i*>(&hREC[4 * static_cast<size_t>(pos - LC)]);
+            rec = ld4(&hREC[4 * static_cast<size_t>(pos - LC)]);
           }
         }
         const bool live = in && (rem > 0 || pl > 0);
@@ -359,8 +375,8 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
     n_live -= 1;
     if (sdepth == SCAP) { fail(FCS_EOVERFLOW, t); return; }
     if (lane == 0) {
-      if (sdepth < kStackLds) *reinterpret_cast<v4i*>(&smem[O_STK + 4 * sdepth]) = rec;
-      else *reinterpret_cast<v4i*>(&hSTK[4 * static_cast<size_t>(sdepth - kStackLds)]) = rec;
+      if (sdepth < kStackLds) st4(&smem[O_STK + 4 * sdepth], rec);
+      else st4(&hSTK[4 * static_cast<size_t>(sdepth - kStackLds)], rec);
       rem_pl_store(pos, -1, 0);
     }
     wave_sync();
@@ -371,16 +387,16 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   };
 
   // =============================== slots 1..T ========================================
-  for (int t = 1; t <= T && !err; ++t) {
+  for (int t = 1; LIKELY(t <= T) && LIKELY(!err); ++t) {
     int x = 0;  // this slot's contribution to the statistics, one counter per lane
 
     // ---- 1. arrivals ---------------------------------------------------------------
     const int wi = (t - 1) & (kWave - 1);
-    if (wi == 0) {
+    if (UNLIKELY(wi == 0)) {
       int n, b;
       draw_slot(static_cast<uint32_t>(t), n, b);
       win = n | (b << 16);
-      if (arrived >= 0x7ffe0000u) fail(FCS_EOVERFLOW, t);
+      if (UNLIKELY(arrived >= 0x7ffe0000u)) fail(FCS_EOVERFLOW, t);
       if (arr_rec) {  // arrival slots of the requests of this window, by arrival id
         const int tt = t + lane;
         const int ne = tt <= T ? n : 0;
@@ -400,13 +416,13 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
       int qlen = sdepth + static_cast<int>(arrived - fresh_next);
       int room = greedy ? qlen : min(B_t, qlen);
       int admitted = 0;
-      while (room > 0 && !err) {
+      while (room > 0 && LIKELY(!err)) {
         const bool from_stack = sdepth > 0;
         int idx = 0;
         if (!from_stack) {
-          if (static_cast<int>(fresh_next - fb_base) >= fb_count) refill_block();
+          if (UNLIKELY(static_cast<int>(fresh_next - fb_base) >= fb_count)) refill_block();
           idx = static_cast<int>(fresh_next - fb_base);
-          if (idx >= fb_count) { fail(FCS_ESTATE, t); break; }
+          if (UNLIKELY(idx >= fb_count)) { fail(FCS_ESTATE, t); break; }
         }
         if (greedy) {
           if (head_l < 0) {
@@ -419,17 +435,17 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
           }
           if (U + n_live + head_l + 1 > M) break;
         }
-        if (n_slots == CAP) {
+        if (UNLIKELY(n_slots == CAP)) {
           if (n_live < n_slots) compact();
           if (n_slots == CAP) { fail(FCS_EOVERFLOW, t); break; }
         }
         const int pos = n_slots;
         int l;
-        if (from_stack) {
+        if (UNLIKELY(from_stack)) {
           const int d = sdepth - 1;
           v4i rec;
-          if (d < kStackLds) rec = *reinterpret_cast<const v4i*>(&smem[O_STK + 4 * d]);
-          else rec = *reinterpret_cast<const v4i*>(&hSTK[4 * static_cast<size_t>(d - kStackLds)]);
+          if (d < kStackLds) rec = ld4(&smem[O_STK + 4 * d]);
+          else rec = ld4(&hSTK[4 * static_cast<size_t>(d - kStackLds)]);
           l = rfl(rec.x);
           if (lane == 0) slot_store(pos, -1, l, rec);
           sdepth = d;
@@ -455,13 +471,13 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
     }
 
     // ---- 3. overflow: evict newest while the provisioned usage exceeds M --------------------
-    if (U + n_live > M) {
+    if (UNLIKELY(U + n_live > M)) {
       int ev = 0;
       do { evict_newest(t); ev += 1; } while (U + n_live > M && !err);
       x = wrl(ev, SL_EVICT, x);
       x = wrl(1, SL_OVF, x);
     }
-    if (err) break;
+    if (UNLIKELY(err)) break;
     const int qlen = sdepth + static_cast<int>(arrived - fresh_next);
 
     // ---- 4a. chunked prefill under the token budget, activation order -----------------------
@@ -475,7 +491,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
       while (todo > 0 && budget > 0 && base < n_slots) {
         const int pos = base + lane;
         int pl, ov;
-        if (base < LC) { pl = smem[O_PL + pos]; ov = smem[O_REC + 4 * pos + 1]; }
+        if (LIKELY(base < LC)) { pl = smem[O_PL + pos]; ov = smem[O_REC + 4 * pos + 1]; }
         else if (pos < n_slots) { pl = hPL[pos - LC]; ov = hREC[4 * static_cast<size_t>(pos - LC) + 1]; }
         else { pl = 0; ov = 0; }
         uint64_t m = __ballot(pl > 0);
@@ -496,7 +512,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
             new_dec += 1;
           } else {
             if (lane == 0) {
-              if (p < LC) smem[O_PL + p] = left; else hPL[p - LC] = left;
+              if (LIKELY(p < LC)) smem[O_PL + p] = left; else hPL[p - LC] = left;
             }
             if (first_left < 0) first_left = p;
           }
@@ -516,15 +532,14 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
 
     // ---- 4b. decode growth: one token per decoding request while budget lasts ----------------
     int rel_sum = 0, n_done = 0;  // completions of this slot: released footprint and count
-    // called where lanes flagged `mine` own a request (slot `pos`) that generated its last token
-    auto complete = [&](bool mine, int pos) {
-      const uint64_t m0 = __ballot(mine);
-      if (m0 == 0) return;
+    // called where the lanes of mask m0 (flag `mine`) own a request, in slot `pos`, that generated
+    // its last token in this slot
+    auto complete = [&](bool mine, uint64_t m0, int pos) {
       int relv = 0;
       if (mine) {
         v4i rec;
-        if (pos < LC) rec = *reinterpret_cast<const v4i*>(&smem[O_REC + 4 * pos]);
-        else rec = *reinterpret_cast<const v4i*>(&hREC[4 * static_cast<size_t>(pos - LC)]);
+        if (LIKELY(pos < LC)) rec = ld4(&smem[O_REC + 4 * pos]);
+        else rec = ld4(&hREC[4 * static_cast<size_t>(pos - LC)]);
         relv = rec.x + rec.y;                       // l + o, released at the end of the slot
         const int lat = t - rec.z + 1;              // arrival to completion, both slots counted
         const uint32_t s = lat_lo + static_cast<uint32_t>(lat);
@@ -534,43 +549,73 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
         use_hi += (u < use_lo) ? 1u : 0u;
         use_lo = u;
         lat_max = max(lat_max, lat);
-        if (hist) atomicAdd(&hist[min(lat >> kp.hist_shift, kp.hist_bins - 1)], 1u);
-        if (comp_rec && rec.w < kp.max_requests) comp_rec[rec.w] = t;
+        if (hist_v) atomicAdd(reinterpret_cast<uint32_t*>(hist_v) + min(lat >> hist_shift_v, hist_last_v), 1u);
+        if (comp_v && rec.w < max_req_v) reinterpret_cast<int32_t*>(comp_v)[rec.w] = t;
       }
-      uint64_t m = m0;
-      n_done += __popcll(m);
-      do {
+      n_done += __popcll(m0);
+      rel_sum += rdl(relv, __builtin_ctzll(m0));
+      uint64_t m = m0 & (m0 - 1);
+      while (UNLIKELY(m != 0)) {
         rel_sum += rdl(relv, __builtin_ctzll(m));
         m &= m - 1;
-      } while (m != 0);
+      }
+    };
+    // completes every request of a four-slots-per-lane block whose entry reached zero and turns
+    // the entry into a tombstone
+    auto complete_block = [&](v4i& v, int p0) {
+      bool any = umin4(v) == 0u;
+      uint64_t m = __ballot(any);
+      while (m != 0) {  // one pass unless a lane holds two completions
+        const int c = v.x == 0 ? 0 : (v.y == 0 ? 1 : (v.z == 0 ? 2 : 3));
+        complete(any, m, p0 + c);
+        if (any) {
+          v.x = c == 0 ? -1 : v.x;
+          v.y = c == 1 ? -1 : v.y;
+          v.z = c == 2 ? -1 : v.z;
+          v.w = c == 3 ? -1 : v.w;
+        }
+        any = umin4(v) == 0u;
+        m = __ballot(any);
+      }
     };
 
     int advanced;  // requests already decoding that got a token
-    if (budget >= n_dec) {
+    if (LIKELY(budget >= n_dec)) {
       advanced = n_dec;
       const int lim = min(n_slots, LC);
-      for (int b0 = 0; b0 < lim; b0 += kLdsBlock) {
-        const int p0 = b0 + (lane << 2);
-        v4i v = *reinterpret_cast<const v4i*>(&smem[p0]);
-        v -= 1;
-        if (__ballot(umin4(v) == 0u) != 0) {
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            const bool d = v[c] == 0;
-            complete(d, p0 + c);
-            if (d) v[c] = -1;
-          }
+      {
+        // the first two blocks without a loop: slots past n_slots hold negative entries
+        const int p0 = lane << 2;
+        const bool two = LC > kLdsBlock;
+        v4i a = ld4(&smem[p0]);
+        v4i b = {-1, -1, -1, -1};
+        if (LIKELY(two)) b = ld4(&smem[kLdsBlock + p0]);
+        a -= 1;
+        b -= 1;
+        if (UNLIKELY(__ballot(min(umin4(a), umin4(b)) == 0u) != 0)) {
+          complete_block(a, p0);
+          complete_block(b, kLdsBlock + p0);
         }
-        *reinterpret_cast<v4i*>(&smem[p0]) = v;
+        st4(&smem[p0], a);
+        if (LIKELY(two)) st4(&smem[kLdsBlock + p0], b);
         wave_sync();
       }
-      for (int base = LC; base < n_slots; base += kWave) {
+      for (int b0 = 2 * kLdsBlock; UNLIKELY(b0 < lim); b0 += kLdsBlock) {
+        const int p0 = b0 + (lane << 2);
+        v4i v = ld4(&smem[p0]);
+        v -= 1;
+        if (__ballot(umin4(v) == 0u) != 0) complete_block(v, p0);
+        st4(&smem[p0], v);
+        wave_sync();
+      }
+      for (int base = LC; UNLIKELY(base < n_slots); base += kWave) {
         const int pos = base + lane;
         const bool in = pos < n_slots;
         int v = in ? hREM[pos - LC] : -1;
         v -= 1;
         const bool d = in && v == 0;
-        complete(d, pos);
+        const uint64_t dm = __ballot(d);
+        if (dm != 0) complete(d, dm, pos);
         if (in) hREM[pos - LC] = d ? -1 : v;
         wave_sync();
       }
@@ -592,12 +637,13 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
         const bool old = dec && !fresh;
         const uint64_t om = __ballot(old);
         const bool go = fresh || (old && lanes_below(om) < left);
-        const int took = min(__popcll(om), left);
+        const int took = min(static_cast<int>(__popcll(om)), left);
         left -= took;
         advanced += took;
         if (go) v -= 1;
         const bool d = go && v == 0;
-        complete(d, pos);
+        const uint64_t dm = __ballot(d);
+        if (dm != 0) complete(d, dm, pos);
         if (go) {
           if (base < LC) smem[pos] = d ? -1 : v; else hREM[pos - LC] = d ? -1 : v;
         }
@@ -621,7 +667,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
       acc_lo = s;
       mx = max(mx, x);
     }
-    if (kp.trace_every > 0 && --trace_left == 0) {
+    if (UNLIKELY(--trace_left == 0)) {
       trace_left = kp.trace_every;
       if (lane == 0) {
         if (kp.out.trace_q) kp.out.trace_q[static_cast<size_t>(path) * kp.n_trace + trace_idx] = qlen;
@@ -634,7 +680,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
     U -= rel_sum;
     n_live -= n_done;
     n_dec -= n_done;
-    if (n_slots - n_live >= kCompactSlack) compact();
+    if (UNLIKELY(n_slots - n_live >= kCompactSlack)) compact();
   }
 
   // ---- epilogue: digest of the final state, counters --------------------------------------------
