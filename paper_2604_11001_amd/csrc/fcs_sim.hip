@@ -21,6 +21,8 @@
 //                statistics accumulate in lanes of a few vector registers.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "fcs_internal.h"
 
 namespace fcs {
@@ -103,6 +105,15 @@ __device__ __forceinline__ void st4(int32_t* p, v4i v) {
   *reinterpret_cast<v4i*>(__builtin_assume_aligned(p, 16)) = v;
 }
 
+// decode growth of four slots: entries of decoding requests (positive) lose one, others stay
+__device__ __forceinline__ void dec4(v4i& v) {
+  // max(v - 1, min(v, 0)) = median(v - 1, v, 0) is v - 1 for v > 0 and v otherwise
+  v.x = max(v.x - 1, min(v.x, 0));
+  v.y = max(v.y - 1, min(v.y, 0));
+  v.z = max(v.z - 1, min(v.z, 0));
+  v.w = max(v.w - 1, min(v.w, 0));
+}
+
 __device__ __forceinline__ uint32_t umin4(v4i v) {
   return min(min(static_cast<uint32_t>(v.x), static_cast<uint32_t>(v.y)),
              min(static_cast<uint32_t>(v.z), static_cast<uint32_t>(v.w)));
@@ -136,11 +147,11 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
 #define hSTK (hREM + static_cast<size_t>(F_NFIELDS) * HC)
 
   // ---- record accessors (uniform position: every lane reads the same record) ---------
-  auto rec_load = [&](int pos) -> v4i {
+  auto rec_load = [&](int pos) __attribute__((always_inline)) -> v4i {
     if (pos < LC) return ld4(&smem[O_REC + 4 * pos]);
     return ld4(&hREC[4 * static_cast<size_t>(pos - LC)]);
   };
-  auto slot_store = [&](int pos, int rem, int pleft, v4i rec) {  // executed by one lane
+  auto slot_store = [&](int pos, int rem, int pleft, v4i rec) __attribute__((always_inline)) {  // executed by one lane
     if (LIKELY(pos < LC)) {
       smem[pos] = rem;
       smem[O_PL + pos] = pleft;
@@ -152,11 +163,11 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
       st4(&hREC[4 * q], rec);
     }
   };
-  auto rem_pl_load = [&](int pos, int& rem, int& pl) {
+  auto rem_pl_load = [&](int pos, int& rem, int& pl) __attribute__((always_inline)) {
     if (LIKELY(pos < LC)) { rem = smem[pos]; pl = smem[O_PL + pos]; }
     else { rem = hREM[pos - LC]; pl = hPL[pos - LC]; }
   };
-  auto rem_pl_store = [&](int pos, int rem, int pl) {
+  auto rem_pl_store = [&](int pos, int rem, int pl) __attribute__((always_inline)) {
     if (LIKELY(pos < LC)) { smem[pos] = rem; smem[O_PL + pos] = pl; }
     else { hREM[pos - LC] = rem; hPL[pos - LC] = pl; }
   };
@@ -207,13 +218,13 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   int lat_max = 0;
   int trace_left = kp.trace_every > 0 ? kp.trace_every : 0x7fffffff, trace_idx = 0;  // T < 2^30
 
-  auto fail = [&](int code, int t) {
+  auto fail = [&](int code, int t) __attribute__((always_inline)) {
     if (!err) { err = code; err_step = t; }
   };
 
   // n_t and B_t of slot t0 + lane (Section 2.1: n_t from a known law with mean lambda;
   // Theorem 2: B_t i.i.d. bounded integers with mean b)
-  auto draw_slot = [&](uint32_t t0, int& n_out, int& b_out) {
+  auto draw_slot = [&](uint32_t t0, int& n_out, int& b_out) __attribute__((always_inline)) {
     const DLaw arr = laws[cellp.arrival];
     const uint32_t* __restrict__ arr_thr = kp.blob + arr.off;
     uint32_t w0, w1, w2, w3;
@@ -226,7 +237,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
 
   // Generates the next block of never-activated requests, in arrival order, starting at
   // arrival index fresh_next (requires fresh_next == fb_base + fb_count).
-  auto refill_block = [&]() {
+  auto refill_block = [&]() __attribute__((always_inline)) {
     fb_base = fresh_next;
     fb_count = 0;
     while (fb_count == 0 && rd_t <= static_cast<uint32_t>(T)) {
@@ -296,7 +307,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   };
 
   // Order-preserving removal of dead slots.
-  auto compact = [&]() {
+  auto compact = [&]() __attribute__((always_inline)) {
     int out = 0, new_pf = -1;
     if (n_slots <= LC) {
       for (int base = 0; base < n_slots; base += kWave) {
@@ -358,7 +369,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
 
   // Evicts the most recently activated request (Section 3.3: last in, first out); it loses
   // its progress and goes back to the front of Q.
-  auto evict_newest = [&](int t) {
+  auto evict_newest = [&](int t) __attribute__((always_inline)) {
     int pos = n_slots - 1;
     int rem = 0, pleft = 0;
     for (; pos >= 0; --pos) {
@@ -387,35 +398,119 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   };
 
   // =============================== slots 1..T ========================================
-  for (int t = 1; LIKELY(t <= T) && LIKELY(!err); ++t) {
-    int x = 0;  // this slot's contribution to the statistics, one counter per lane
+  // Two renditions of one slot.  `general_slot` handles every case (spill tier, evictions, budget
+  // stalls, table refills, compaction) and can pick a slot up at any of its phases.  The loop
+  // below it is the same slot restricted to what almost every slot needs (everything in LDS, no
+  // eviction, no stall); when a slot needs more it hands over to `general_slot` at the phase it
+  // has reached.  Variables of the slot in flight are shared between the two.
+  int t = 1;
+  int phase = 0;  // 0 slot start, 1 admission, 3 overflow check, 4 decode pass, 6 compaction only
+  int x = 0;      // this slot's contribution to the statistics, one counter per lane
+  int room = 0, admitted = 0, budget = 0, new_dec = 0;
+  int rel_sum = 0, n_done = 0;  // completions of this slot: released footprint and count
 
+  // called where the lanes of mask m0 (flag `mine`) own a request, in slot `pos`, that generated
+  // its last token in this slot
+  auto complete = [&](bool mine, uint64_t m0, int pos) __attribute__((always_inline)) {
+    int relv = 0;
+    if (mine) {
+      v4i rec;
+      if (LIKELY(pos < LC)) rec = ld4(&smem[O_REC + 4 * pos]);
+      else rec = ld4(&hREC[4 * static_cast<size_t>(pos - LC)]);
+      relv = rec.x + rec.y;                       // l + o, released at the end of the slot
+      const int lat = t - rec.z + 1;              // arrival to completion, both slots counted
+      const uint32_t s = lat_lo + static_cast<uint32_t>(lat);
+      lat_hi += (s < lat_lo) ? 1u : 0u;
+      lat_lo = s;
+      const uint32_t u = use_lo + static_cast<uint32_t>(rec.y);
+      use_hi += (u < use_lo) ? 1u : 0u;
+      use_lo = u;
+      lat_max = max(lat_max, lat);
+      if (hist_v) atomicAdd(reinterpret_cast<uint32_t*>(hist_v) + min(lat >> hist_shift_v, hist_last_v), 1u);
+      if (comp_v && rec.w < max_req_v) reinterpret_cast<int32_t*>(comp_v)[rec.w] = t;
+    }
+    n_done += static_cast<int>(__popcll(m0));
+    rel_sum += rdl(relv, __builtin_ctzll(m0));
+    uint64_t m = m0 & (m0 - 1);
+    while (UNLIKELY(m != 0)) {
+      rel_sum += rdl(relv, __builtin_ctzll(m));
+      m &= m - 1;
+    }
+  };
+  // completes every request of a four-slots-per-lane block whose entry reached zero and turns
+  // the entry into a tombstone
+  auto complete_block = [&](v4i& v, int p0) __attribute__((always_inline)) {
+    bool any = umin4(v) == 0u;
+    uint64_t m = __ballot(any);
+    while (m != 0) {  // one pass unless a lane holds two completions
+      const int c = v.x == 0 ? 0 : (v.y == 0 ? 1 : (v.z == 0 ? 2 : 3));
+      complete(any, m, p0 + c);
+      if (any) {
+        v.x = c == 0 ? -1 : v.x;
+        v.y = c == 1 ? -1 : v.y;
+        v.z = c == 2 ? -1 : v.z;
+        v.w = c == 3 ? -1 : v.w;
+      }
+      any = umin4(v) == 0u;
+      m = __ballot(any);
+    }
+  };
+  // step 5 (Section 2.1: U_t after processing, before completed requests leave) and step 6
+  auto measure_and_release = [&](int tokens, int qlen) __attribute__((always_inline)) {
+    U += tokens;
+    n_dec += new_dec;
+    x = wrl(U, SL_SUM_U, x);
+    x = wrl(n_live, SL_SUM_P, x);
+    x = wrl(qlen, SL_SUM_Q, x);
+    x = wrl(tokens, SL_DEC_TOK, x);
+    if (n_done) x = wrl(n_done, SL_DONE, x);
+    const uint32_t s = acc_lo + static_cast<uint32_t>(x);
+    acc_hi += (s < acc_lo) ? 1u : 0u;
+    acc_lo = s;
+    mx = max(mx, x);
+    if (UNLIKELY(--trace_left == 0)) {
+      trace_left = kp.trace_every;
+      if (lane == 0) {
+        if (kp.out.trace_q) kp.out.trace_q[static_cast<size_t>(path) * kp.n_trace + trace_idx] = qlen;
+        if (kp.out.trace_u) kp.out.trace_u[static_cast<size_t>(path) * kp.n_trace + trace_idx] = U;
+      }
+      trace_idx += 1;
+    }
+    // the footprint of completed requests is released at the end of the slot
+    U -= rel_sum;
+    n_live -= n_done;
+    n_dec -= n_done;
+  };
+
+  auto general_slot = [&]() __attribute__((always_inline)) {
     // ---- 1. arrivals ---------------------------------------------------------------
-    const int wi = (t - 1) & (kWave - 1);
-    if (UNLIKELY(wi == 0)) {
-      int n, b;
-      draw_slot(static_cast<uint32_t>(t), n, b);
-      win = n | (b << 16);
-      if (UNLIKELY(arrived >= 0x7ffe0000u)) fail(FCS_EOVERFLOW, t);
-      if (arr_rec) {  // arrival slots of the requests of this window, by arrival id
-        const int tt = t + lane;
-        const int ne = tt <= T ? n : 0;
-        const int excl = wave_incl_sum(ne, lane) - ne;
-        for (int k = 0; k < ne; ++k) {
-          const uint32_t id = arrived + static_cast<uint32_t>(excl + k);
-          if (id < static_cast<uint32_t>(kp.max_requests)) arr_rec[id] = tt;
+    if (phase <= 0) {
+      x = 0;
+      const int wi = (t - 1) & (kWave - 1);
+      if (wi == 0) {
+        int n, b;
+        draw_slot(static_cast<uint32_t>(t), n, b);
+        win = n | (b << 16);
+        if (UNLIKELY(arrived >= 0x7ffe0000u)) fail(FCS_EOVERFLOW, t);
+        if (arr_rec) {  // arrival slots of the requests of this window, by arrival id
+          const int tt = t + lane;
+          const int ne = tt <= T ? n : 0;
+          const int excl = wave_incl_sum(ne, lane) - ne;
+          for (int k = 0; k < ne; ++k) {
+            const uint32_t id = arrived + static_cast<uint32_t>(excl + k);
+            if (id < static_cast<uint32_t>(kp.max_requests)) arr_rec[id] = tt;
+          }
         }
       }
+      const int nb = rdl(win, wi);
+      arrived += static_cast<uint32_t>(nb & 0xffff);
+      const int ql = sdepth + static_cast<int>(arrived - fresh_next);
+      room = greedy ? ql : min(nb >> 16, ql);
+      admitted = 0;
     }
-    const int nb = rdl(win, wi);
-    const int B_t = nb >> 16;
-    arrived += static_cast<uint32_t>(nb & 0xffff);
 
     // ---- 2. admission: FLOW moves min(B_t, |Q|) head requests, GREEDY while the head fits ----
-    {
-      int qlen = sdepth + static_cast<int>(arrived - fresh_next);
-      int room = greedy ? qlen : min(B_t, qlen);
-      int admitted = 0;
+    if (phase <= 1) {
       while (room > 0 && LIKELY(!err)) {
         const bool from_stack = sdepth > 0;
         int idx = 0;
@@ -441,19 +536,19 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
         }
         const int pos = n_slots;
         int l;
-        if (UNLIKELY(from_stack)) {
+        if (from_stack) {
           const int d = sdepth - 1;
           v4i rec;
           if (d < kStackLds) rec = ld4(&smem[O_STK + 4 * d]);
           else rec = ld4(&hSTK[4 * static_cast<size_t>(d - kStackLds)]);
           l = rfl(rec.x);
-          if (lane == 0) slot_store(pos, -1, l, rec);
+          if (lane == 0) slot_store(pos, -rec.y, l, rec);
           sdepth = d;
         } else {
           l = rdl(fb_l, idx);
           if (lane == idx) {
             const v4i rec = {fb_l, fb_o, fb_t, static_cast<int>(fresh_next)};
-            slot_store(pos, -1, fb_l, rec);
+            slot_store(pos, -fb_o, fb_l, rec);
           }
           fresh_next += 1u;
         }
@@ -470,222 +565,151 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
       if (admitted) x = wrl(admitted, SL_ACT, x);
     }
 
-    // ---- 3. overflow: evict newest while the provisioned usage exceeds M --------------------
-    if (UNLIKELY(U + n_live > M)) {
-      int ev = 0;
-      do { evict_newest(t); ev += 1; } while (U + n_live > M && !err);
-      x = wrl(ev, SL_EVICT, x);
-      x = wrl(1, SL_OVF, x);
-    }
-    if (UNLIKELY(err)) break;
-    const int qlen = sdepth + static_cast<int>(arrived - fresh_next);
+    if (phase <= 3) {
+      // ---- 3. overflow: evict newest while the provisioned usage exceeds M ------------------
+      if (UNLIKELY(U + n_live > M)) {
+        int ev = 0;
+        do { evict_newest(t); ev += 1; } while (U + n_live > M && !err);
+        x = wrl(ev, SL_EVICT, x);
+        x = wrl(1, SL_OVF, x);
+      }
+      if (UNLIKELY(err)) return;
 
-    // ---- 4a. chunked prefill under the token budget, activation order -----------------------
-    int budget = kp.tau;
-    int new_dec = 0;
-    if (n_pf > 0) {
-      int todo = n_pf;
-      int base = pf_first & ~(kWave - 1);
-      int first_left = -1;
-      const int budget0 = budget;
-      while (todo > 0 && budget > 0 && base < n_slots) {
-        const int pos = base + lane;
-        int pl, ov;
-        if (LIKELY(base < LC)) { pl = smem[O_PL + pos]; ov = smem[O_REC + 4 * pos + 1]; }
-        else if (pos < n_slots) { pl = hPL[pos - LC]; ov = hREC[4 * static_cast<size_t>(pos - LC) + 1]; }
-        else { pl = 0; ov = 0; }
-        uint64_t m = __ballot(pl > 0);
-        while (m != 0 && budget > 0) {
-          const int i = __builtin_ctzll(m);
-          m &= m - 1;
-          const int p = base + i;
-          int left = rdl(pl, i);
-          const int d = min(min(kp.chunk, left), budget);
-          left -= d;
-          budget -= d;
-          todo -= 1;
-          if (left == 0) {
-            // the chunk that ends the prompt yields token 1: the entry becomes o here and the
-            // decode pass of this slot makes it o - 1
-            const int o = rdl(ov, i);
-            if (lane == 0) rem_pl_store(p, o, 0);
-            new_dec += 1;
-          } else {
-            if (lane == 0) {
-              if (LIKELY(p < LC)) smem[O_PL + p] = left; else hPL[p - LC] = left;
+      // ---- 4a. chunked prefill under the token budget, activation order ---------------------
+      budget = kp.tau;
+      new_dec = 0;
+      if (n_pf > 0) {
+        int todo = n_pf;
+        int base = pf_first & ~(kWave - 1);
+        int first_left = -1;
+        while (todo > 0 && budget > 0 && base < n_slots) {
+          const int pos = base + lane;
+          int pl, ov;
+          if (LIKELY(base < LC)) { pl = smem[O_PL + pos]; ov = smem[O_REC + 4 * pos + 1]; }
+          else if (pos < n_slots) { pl = hPL[pos - LC]; ov = hREC[4 * static_cast<size_t>(pos - LC) + 1]; }
+          else { pl = 0; ov = 0; }
+          uint64_t m = __ballot(pl > 0);
+          while (m != 0 && budget > 0) {
+            const int i = __builtin_ctzll(m);
+            m &= m - 1;
+            const int p = base + i;
+            int left = rdl(pl, i);
+            const int d = min(min(kp.chunk, left), budget);
+            left -= d;
+            budget -= d;
+            todo -= 1;
+            if (left == 0) {
+              // the chunk that ends the prompt yields token 1: the entry becomes o here and the
+              // decode pass of this slot makes it o - 1
+              const int o = rdl(ov, i);
+              if (lane == 0) rem_pl_store(p, o, 0);
+              new_dec += 1;
+            } else {
+              if (lane == 0) {
+                if (LIKELY(p < LC)) smem[O_PL + p] = left; else hPL[p - LC] = left;
+              }
+              if (first_left < 0) first_left = p;
             }
-            if (first_left < 0) first_left = p;
           }
+          wave_sync();
+          if (m != 0) {  // budget ran out inside this chunk
+            if (first_left < 0) first_left = base + __builtin_ctzll(m);
+            break;
+          }
+          base += kWave;
         }
-        wave_sync();
-        if (m != 0) {  // budget ran out inside this chunk
-          if (first_left < 0) first_left = base + __builtin_ctzll(m);
-          break;
-        }
-        base += kWave;
+        if (first_left >= 0) pf_first = first_left;
+        else pf_first = (todo > 0) ? min(base, n_slots) : n_slots;
+        n_pf -= new_dec;
+        x = wrl(kp.tau - budget, SL_PF_TOK, x);
       }
-      if (first_left >= 0) pf_first = first_left;
-      else pf_first = (todo > 0) ? min(base, n_slots) : n_slots;
-      n_pf -= new_dec;
-      x = wrl(budget0 - budget, SL_PF_TOK, x);
     }
 
-    // ---- 4b. decode growth: one token per decoding request while budget lasts ----------------
-    int rel_sum = 0, n_done = 0;  // completions of this slot: released footprint and count
-    // called where the lanes of mask m0 (flag `mine`) own a request, in slot `pos`, that generated
-    // its last token in this slot
-    auto complete = [&](bool mine, uint64_t m0, int pos) {
-      int relv = 0;
-      if (mine) {
-        v4i rec;
-        if (LIKELY(pos < LC)) rec = ld4(&smem[O_REC + 4 * pos]);
-        else rec = ld4(&hREC[4 * static_cast<size_t>(pos - LC)]);
-        relv = rec.x + rec.y;                       // l + o, released at the end of the slot
-        const int lat = t - rec.z + 1;              // arrival to completion, both slots counted
-        const uint32_t s = lat_lo + static_cast<uint32_t>(lat);
-        lat_hi += (s < lat_lo) ? 1u : 0u;
-        lat_lo = s;
-        const uint32_t u = use_lo + static_cast<uint32_t>(rec.y);
-        use_hi += (u < use_lo) ? 1u : 0u;
-        use_lo = u;
-        lat_max = max(lat_max, lat);
-        if (hist_v) atomicAdd(reinterpret_cast<uint32_t*>(hist_v) + min(lat >> hist_shift_v, hist_last_v), 1u);
-        if (comp_v && rec.w < max_req_v) reinterpret_cast<int32_t*>(comp_v)[rec.w] = t;
-      }
-      n_done += __popcll(m0);
-      rel_sum += rdl(relv, __builtin_ctzll(m0));
-      uint64_t m = m0 & (m0 - 1);
-      while (UNLIKELY(m != 0)) {
-        rel_sum += rdl(relv, __builtin_ctzll(m));
-        m &= m - 1;
-      }
-    };
-    // completes every request of a four-slots-per-lane block whose entry reached zero and turns
-    // the entry into a tombstone
-    auto complete_block = [&](v4i& v, int p0) {
-      bool any = umin4(v) == 0u;
-      uint64_t m = __ballot(any);
-      while (m != 0) {  // one pass unless a lane holds two completions
-        const int c = v.x == 0 ? 0 : (v.y == 0 ? 1 : (v.z == 0 ? 2 : 3));
-        complete(any, m, p0 + c);
-        if (any) {
-          v.x = c == 0 ? -1 : v.x;
-          v.y = c == 1 ? -1 : v.y;
-          v.z = c == 2 ? -1 : v.z;
-          v.w = c == 3 ? -1 : v.w;
+    if (phase <= 4) {
+      const int qlen = sdepth + static_cast<int>(arrived - fresh_next);
+      // ---- 4b. decode growth: one token per decoding request while budget lasts --------------
+      rel_sum = 0;
+      n_done = 0;
+      int advanced;  // requests already decoding that got a token
+      if (LIKELY(budget >= n_dec)) {
+        advanced = n_dec;
+        const int lim = min(n_slots, LC);
+        for (int b0 = 0; b0 < lim; b0 += kLdsBlock) {
+          const int p0 = b0 + (lane << 2);
+          v4i v = ld4(&smem[p0]);
+          dec4(v);
+          if (__ballot(umin4(v) == 0u) != 0) complete_block(v, p0);
+          st4(&smem[p0], v);
+          wave_sync();
         }
-        any = umin4(v) == 0u;
-        m = __ballot(any);
-      }
-    };
-
-    int advanced;  // requests already decoding that got a token
-    if (LIKELY(budget >= n_dec)) {
-      advanced = n_dec;
-      const int lim = min(n_slots, LC);
-      {
-        // the first two blocks without a loop: slots past n_slots hold negative entries
-        const int p0 = lane << 2;
-        const bool two = LC > kLdsBlock;
-        v4i a = ld4(&smem[p0]);
-        v4i b = {-1, -1, -1, -1};
-        if (LIKELY(two)) b = ld4(&smem[kLdsBlock + p0]);
-        a -= 1;
-        b -= 1;
-        if (UNLIKELY(__ballot(min(umin4(a), umin4(b)) == 0u) != 0)) {
-          complete_block(a, p0);
-          complete_block(b, kLdsBlock + p0);
+        for (int base = LC; base < n_slots; base += kWave) {
+          const int pos = base + lane;
+          const bool in = pos < n_slots;
+          int v = in ? hREM[pos - LC] : -1;
+          v -= (v > 0) ? 1 : 0;
+          const bool d = in && v == 0;
+          const uint64_t dm = __ballot(d);
+          if (dm != 0) complete(d, dm, pos);
+          if (in) hREM[pos - LC] = d ? -1 : v;
+          wave_sync();
         }
-        st4(&smem[p0], a);
-        if (LIKELY(two)) st4(&smem[kLdsBlock + p0], b);
-        wave_sync();
-      }
-      for (int b0 = 2 * kLdsBlock; UNLIKELY(b0 < lim); b0 += kLdsBlock) {
-        const int p0 = b0 + (lane << 2);
-        v4i v = ld4(&smem[p0]);
-        v -= 1;
-        if (__ballot(umin4(v) == 0u) != 0) complete_block(v, p0);
-        st4(&smem[p0], v);
-        wave_sync();
-      }
-      for (int base = LC; UNLIKELY(base < n_slots); base += kWave) {
-        const int pos = base + lane;
-        const bool in = pos < n_slots;
-        int v = in ? hREM[pos - LC] : -1;
-        v -= 1;
-        const bool d = in && v == 0;
-        const uint64_t dm = __ballot(d);
-        if (dm != 0) complete(d, dm, pos);
-        if (in) hREM[pos - LC] = d ? -1 : v;
-        wave_sync();
-      }
-    } else {
-      // budget binds: the first `budget` already-decoding requests in activation order advance;
-      // requests that finished their prompt in this slot (entry == o) take token 1 for free
-      int left = budget;
-      advanced = 0;
-      for (int base = 0; base < n_slots; base += kWave) {
-        const int pos = base + lane;
-        const bool in = pos < n_slots;
-        int v = -1, ov = 0;
-        if (in) {
-          if (base < LC) { v = smem[pos]; ov = smem[O_REC + 4 * pos + 1]; }
-          else { v = hREM[pos - LC]; ov = hREC[4 * static_cast<size_t>(pos - LC) + 1]; }
+      } else {
+        // budget binds: the first `budget` already-decoding requests in activation order advance;
+        // requests that finished their prompt in this slot (entry == o) take token 1 for free
+        int left = budget;
+        advanced = 0;
+        for (int base = 0; base < n_slots; base += kWave) {
+          const int pos = base + lane;
+          const bool in = pos < n_slots;
+          int v = -1, ov = 0;
+          if (in) {
+            if (base < LC) { v = smem[pos]; ov = smem[O_REC + 4 * pos + 1]; }
+            else { v = hREM[pos - LC]; ov = hREC[4 * static_cast<size_t>(pos - LC) + 1]; }
+          }
+          const bool dec = v > 0;
+          const bool fresh = dec && new_dec > 0 && v == ov;
+          const bool old = dec && !fresh;
+          const uint64_t om = __ballot(old);
+          const bool go = fresh || (old && lanes_below(om) < left);
+          const int took = min(static_cast<int>(__popcll(om)), left);
+          left -= took;
+          advanced += took;
+          if (go) v -= 1;
+          const bool d = go && v == 0;
+          const uint64_t dm = __ballot(d);
+          if (dm != 0) complete(d, dm, pos);
+          if (go) {
+            if (base < LC) smem[pos] = d ? -1 : v; else hREM[pos - LC] = d ? -1 : v;
+          }
+          wave_sync();
         }
-        const bool dec = v > 0;
-        const bool fresh = dec && new_dec > 0 && v == ov;
-        const bool old = dec && !fresh;
-        const uint64_t om = __ballot(old);
-        const bool go = fresh || (old && lanes_below(om) < left);
-        const int took = min(static_cast<int>(__popcll(om)), left);
-        left -= took;
-        advanced += took;
-        if (go) v -= 1;
-        const bool d = go && v == 0;
-        const uint64_t dm = __ballot(d);
-        if (dm != 0) complete(d, dm, pos);
-        if (go) {
-          if (base < LC) smem[pos] = d ? -1 : v; else hREM[pos - LC] = d ? -1 : v;
-        }
-        wave_sync();
+        x = wrl(n_dec - advanced, SL_STALLED, x);
       }
-      x = wrl(n_dec - advanced, SL_STALLED, x);
+      measure_and_release(advanced + new_dec, qlen);
     }
-    const int tokens = advanced + new_dec;
-    U += tokens;
-    n_dec += new_dec;
+    if (n_slots - n_live >= kCompactSlack) compact();
+  };
 
-    // ---- 5. measure (Section 2.1: U_t after processing, before completed requests leave) --------
-    x = wrl(U, SL_SUM_U, x);
-    x = wrl(n_live, SL_SUM_P, x);
-    x = wrl(qlen, SL_SUM_Q, x);
-    x = wrl(tokens, SL_DEC_TOK, x);
-    if (n_done) x = wrl(n_done, SL_DONE, x);
-    {
-      const uint32_t s = acc_lo + static_cast<uint32_t>(x);
-      acc_hi += (s < acc_lo) ? 1u : 0u;
-      acc_lo = s;
-      mx = max(mx, x);
-    }
-    if (UNLIKELY(--trace_left == 0)) {
-      trace_left = kp.trace_every;
-      if (lane == 0) {
-        if (kp.out.trace_q) kp.out.trace_q[static_cast<size_t>(path) * kp.n_trace + trace_idx] = qlen;
-        if (kp.out.trace_u) kp.out.trace_u[static_cast<size_t>(path) * kp.n_trace + trace_idx] = U;
-      }
-      trace_idx += 1;
-    }
+  // The common slot (everything in LDS, no eviction, no stall) as hand-scheduled assembly; runs
+  // slots until one needs the general code and returns with `phase` set.
+  const int lds_base = static_cast<int>(
+      reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) int32_t*)smem));
+  auto fast_slots = [&]() __attribute__((always_inline)) {
+#include "fcs_fast_slots.inc"
+  };
 
-    // ---- 6. complete: the footprint is released at the end of the slot -------------------------
-    U -= rel_sum;
-    n_live -= n_done;
-    n_dec -= n_done;
-    if (UNLIKELY(n_slots - n_live >= kCompactSlack)) compact();
+  const bool fast_ok = LC >= 2 * kLdsBlock;
+  while (t <= T && !err) {
+    general_slot();
+    ++t;
+    phase = 0;
+    if (UNLIKELY(!fast_ok) || UNLIKELY(n_slots > LC) || UNLIKELY(err)) continue;
+    fast_slots();
   }
 
   // ---- epilogue: digest of the final state, counters --------------------------------------------
   uint64_t h = 14695981039346656037ull;
-  auto mix = [&](uint64_t w) { h = (h ^ w) * 1099511628211ull; };
+  auto mix = [&](uint64_t w) __attribute__((always_inline)) { h = (h ^ w) * 1099511628211ull; };
   if (!err) {
     compact();
     mix(static_cast<uint64_t>(n_slots));
