@@ -183,7 +183,7 @@ static int geometry_for(fcs_engine* h, int64_t n_replicas, int32_t* lcap, int32_
     int64_t per_cu = (n_paths + 255) / 256;
     per_cu = std::min<int64_t>(std::max<int64_t>(per_cu, 4), 12);
     const int64_t words = (160 * 1024 / per_cu) / 4 - S_NFIELDS * kStackLds - kScratchWords;
-    lc = static_cast<int32_t>(words / F_NFIELDS / kLdsBlock * kLdsBlock);
+    lc = static_cast<int32_t>(words / kLdsWordsPerSlot / kLdsBlock * kLdsBlock);
     lc = std::min(std::max(lc, kLdsBlock), 2048);
   }
   lc = static_cast<int32_t>(std::min<int64_t>(lc, static_cast<int64_t>(round_up(max_active, kLdsBlock))));
@@ -198,7 +198,7 @@ int fcs_workspace_bytes(fcs_handle h, int64_t n_replicas, size_t* bytes) {
   int32_t lc, hc, hs;
   int rc = geometry_for(h, n_replicas, &lc, &hc, &hs);
   if (rc != FCS_OK) return rc;
-  const size_t stride = static_cast<size_t>(F_NFIELDS) * hc + static_cast<size_t>(S_NFIELDS) * hs;
+  const size_t stride = static_cast<size_t>(kSpillWordsPerSlot) * hc + static_cast<size_t>(S_NFIELDS) * hs;
   *bytes = h->blob_bytes_padded + round_up(stride * sizeof(int32_t) * n_replicas * h->n_cells, 256) + 256;
   return FCS_OK;
 }
@@ -212,7 +212,7 @@ int fcs_bind(fcs_handle h, void* ws, size_t bytes, int64_t n_replicas, const fcs
   if (bytes < need) return FCS_ENOMEM;
   rc = geometry_for(h, n_replicas, &h->lcap, &h->hcap, &h->hscap);
   if (rc != FCS_OK) return rc;
-  h->spill_stride = static_cast<int64_t>(F_NFIELDS) * h->hcap + static_cast<int64_t>(S_NFIELDS) * h->hscap;
+  h->spill_stride = static_cast<int64_t>(kSpillWordsPerSlot) * h->hcap + static_cast<int64_t>(S_NFIELDS) * h->hscap;
   hipError_t e = hipMemcpyAsync(ws, h->blob.data(), h->blob.size() * sizeof(uint32_t),
                                 hipMemcpyHostToDevice, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return FCS_EDEVICE;

@@ -25,10 +25,12 @@ struct DCell {
   uint32_t b_frac_thr;
 };
 
-// Fields of one active-set slot (structure of arrays, int32 each).
-enum { F_REM = 0, F_PLEFT, F_L, F_O, F_TARR, F_ID, F_NFIELDS };
-// Fields of one entry of the stack of evicted requests.
-enum { S_ID = 0, S_L, S_O, S_TARR, S_NFIELDS };
+// Words of one active-set slot: in LDS {END, footprint} pairs, PLEFT and the 4-word record; in the
+// spill region END, PLEFT and the record.
+constexpr int kLdsWordsPerSlot = 7;
+constexpr int kSpillWordsPerSlot = 6;
+// Words of one entry of the stack of evicted requests (its record).
+constexpr int S_NFIELDS = 4;
 
 constexpr int kWave = 64;
 constexpr int kGuideBits = 12;
@@ -49,14 +51,14 @@ struct KParams {
   int32_t n_steps;
   uint32_t seed_lo, seed_hi;
   int32_t lcap, hcap, hscap;  // LDS slots, spill slots, spill stack entries (per path)
-  int32_t* spill;             // per path: F_NFIELDS*hcap + S_NFIELDS*hscap words
+  int32_t* spill;             // per path: kSpillWordsPerSlot*hcap + S_NFIELDS*hscap words
   int64_t spill_stride;       // words per path
   int32_t trace_every, n_trace, hist_bins, hist_shift, max_requests;
   int32_t n_paths;
   fcs_outputs out;
 };
 
-inline int lds_words(int lcap) { return F_NFIELDS * lcap + S_NFIELDS * kStackLds + kScratchWords; }
+inline int lds_words(int lcap) { return kLdsWordsPerSlot * lcap + S_NFIELDS * kStackLds + kScratchWords; }
 
 // Defined in fcs_sim.hip; launches one single-wavefront workgroup per path.
 int launch_sim(const KParams& kp, void* stream);

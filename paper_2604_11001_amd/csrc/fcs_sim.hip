@@ -2,16 +2,25 @@
 // model (Section 2.1) under Algorithm 2 or its greedy limit, for slots 1..T.
 //
 // Data layout per path
-//   active set   slots in activation order; completed requests leave dead slots behind
-//                ("tombstones") that an order-preserving compaction removes once kCompactSlack
-//                of them have accumulated.  Slots [0, lcap) live in LDS, slots
-//                [lcap, lcap+hcap) in a per-path spill region of the workspace.  Per slot:
-//                  REM    o - j while decoding, negative otherwise.  The decode growth of a
-//                         slot (Section 2.1: one more token per active request) is one
-//                         decrement per slot of this array, four slots per lane per pass;
-//                         a request completes when its entry reaches zero.
-//                  PLEFT  prompt tokens still to prefill (0 once decoding, 0 for tombstones)
-//                  REC    {l, o, arrival slot, id}, read when the request completes or is evicted
+//   active set   slots in activation order; requests that left stay behind as dead slots until an
+//                order-preserving compaction removes them (once kCompactSlack have accumulated).
+//                Slots [0, lcap) live in LDS, slots [lcap, lcap+hcap) in a per-path spill region
+//                of the workspace.  Per slot:
+//                  END    while decoding: the slot in which the request generates its last
+//                         token if no token budget ever binds; -1 while prefilling or unused.
+//                         An entry in [0, current slot) belongs to a request that completed in
+//                         that slot and has not been accounted yet: latency statistics are
+//                         taken when the dead slot is removed, for 64 slots at a time.
+//                         The decode growth of a slot (Section 2.1: one more token per active
+//                         request) therefore costs nothing per request: U grows by the number
+//                         of decoding requests, and the entries are only looked at in slots
+//                         for which the calendar (a bit per slot of the current 64-slot
+//                         window, a superset of the slots with a completion) says so.  A slot
+//                         whose budget binds moves the entries of the stalled requests by one.
+//                  FOOT   l + o, what the request releases when it completes (LDS only, next
+//                         to END: the two are read together)
+//                  PLEFT  prompt tokens still to prefill; meaningful while END is -1 (0 = unused)
+//                  REC    {l, o, arrival slot, id}
 //   waiting queue  requests that were never activated are not stored: arrivals are a pure
 //                function of (seed, replica, slot, index), so the FIFO of fresh requests is
 //                re-generated 64 arrivals at a time when they are admitted.  Evicted requests
@@ -105,20 +114,6 @@ __device__ __forceinline__ void st4(int32_t* p, v4i v) {
   *reinterpret_cast<v4i*>(__builtin_assume_aligned(p, 16)) = v;
 }
 
-// decode growth of four slots: entries of decoding requests (positive) lose one, others stay
-__device__ __forceinline__ void dec4(v4i& v) {
-  // max(v - 1, min(v, 0)) = median(v - 1, v, 0) is v - 1 for v > 0 and v otherwise
-  v.x = max(v.x - 1, min(v.x, 0));
-  v.y = max(v.y - 1, min(v.y, 0));
-  v.z = max(v.z - 1, min(v.z, 0));
-  v.w = max(v.w - 1, min(v.w, 0));
-}
-
-__device__ __forceinline__ uint32_t umin4(v4i v) {
-  return min(min(static_cast<uint32_t>(v.x), static_cast<uint32_t>(v.y)),
-             min(static_cast<uint32_t>(v.z), static_cast<uint32_t>(v.w)));
-}
-
 // lanes of the per-slot statistics vector
 enum { SL_SUM_U = 0, SL_SUM_P, SL_SUM_Q, SL_DEC_TOK, SL_ACT, SL_DONE, SL_EVICT, SL_OVF, SL_PF_TOK,
        SL_STALLED, SL_COUNT };
@@ -139,37 +134,51 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   const int CAP = LC + HC;            // slots of the active set
   const int SCAP = kStackLds + HS;    // entries of the evicted stack
   // LDS word offsets
-  const int O_PL = LC, O_REC = 2 * LC, O_STK = F_NFIELDS * LC, O_SCR = O_STK + S_NFIELDS * kStackLds;
+  const int O_PL = 2 * LC, O_REC = 3 * LC, O_STK = kLdsWordsPerSlot * LC, O_SCR = O_STK + S_NFIELDS * kStackLds;
   // spill region of this path
   int32_t* const hREM = kp.spill + static_cast<size_t>(path) * kp.spill_stride;
 #define hPL (hREM + HC)
 #define hREC (hREM + 2 * static_cast<size_t>(HC))
-#define hSTK (hREM + static_cast<size_t>(F_NFIELDS) * HC)
+#define hSTK (hREM + static_cast<size_t>(kSpillWordsPerSlot) * HC)
 
   // ---- record accessors (uniform position: every lane reads the same record) ---------
   auto rec_load = [&](int pos) __attribute__((always_inline)) -> v4i {
     if (pos < LC) return ld4(&smem[O_REC + 4 * pos]);
     return ld4(&hREC[4 * static_cast<size_t>(pos - LC)]);
   };
-  auto slot_store = [&](int pos, int rem, int pleft, v4i rec) __attribute__((always_inline)) {  // executed by one lane
+  // writes a whole slot; executed by one lane
+  auto slot_store = [&](int pos, int end, int pleft, v4i rec) __attribute__((always_inline)) {
     if (LIKELY(pos < LC)) {
-      smem[pos] = rem;
+      smem[2 * pos] = end;
+      smem[2 * pos + 1] = rec.x + rec.y;
       smem[O_PL + pos] = pleft;
       st4(&smem[O_REC + 4 * pos], rec);
     } else {
       const size_t q = static_cast<size_t>(pos - LC);
-      hREM[q] = rem;
+      hREM[q] = end;
       hPL[q] = pleft;
       st4(&hREC[4 * q], rec);
     }
   };
-  auto rem_pl_load = [&](int pos, int& rem, int& pl) __attribute__((always_inline)) {
-    if (LIKELY(pos < LC)) { rem = smem[pos]; pl = smem[O_PL + pos]; }
-    else { rem = hREM[pos - LC]; pl = hPL[pos - LC]; }
+  // a request enters slot pos (in LDS its END entry is -1 already); executed by one lane
+  auto slot_admit = [&](int pos, int pleft, v4i rec) __attribute__((always_inline)) {
+    if (LIKELY(pos < LC)) {
+      smem[O_PL + pos] = pleft;
+      st4(&smem[O_REC + 4 * pos], rec);
+    } else {
+      const size_t q = static_cast<size_t>(pos - LC);
+      hREM[q] = -1;  // the spill region starts out uninitialised
+      hPL[q] = pleft;
+      st4(&hREC[4 * q], rec);
+    }
   };
-  auto rem_pl_store = [&](int pos, int rem, int pl) __attribute__((always_inline)) {
-    if (LIKELY(pos < LC)) { smem[pos] = rem; smem[O_PL + pos] = pl; }
-    else { hREM[pos - LC] = rem; hPL[pos - LC] = pl; }
+  auto end_pl_load = [&](int pos, int& end, int& pl) __attribute__((always_inline)) {
+    if (LIKELY(pos < LC)) { end = smem[2 * pos]; pl = smem[O_PL + pos]; }
+    else { end = hREM[pos - LC]; pl = hPL[pos - LC]; }
+  };
+  auto end_pl_store = [&](int pos, int end, int pl) __attribute__((always_inline)) {
+    if (LIKELY(pos < LC)) { smem[2 * pos] = end; smem[O_PL + pos] = pl; }
+    else { hREM[pos - LC] = end; hPL[pos - LC] = pl; }
   };
 
   // ---- output rows of this path ------------------------------------------------------
@@ -182,11 +191,12 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   if (arr_rec) for (int i = lane; i < kp.max_requests; i += kWave) arr_rec[i] = 0;
   if (comp_rec) for (int i = lane; i < kp.max_requests; i += kWave) comp_rec[i] = 0;
   for (int i = lane; i < LC; i += kWave) {
-    smem[i] = -1;
+    smem[2 * i] = -1;
+    smem[2 * i + 1] = 0;
     smem[O_PL + i] = 0;
   }
   wave_sync();
-  // the completion handler runs in the lanes that own the finished slots: keep what it needs in
+  // completions are accounted in the lanes that hold the dead slots: keep what that needs in
   // vector registers so that it costs no scalar registers in the main loop
   uint64_t hist_v = reinterpret_cast<uint64_t>(hist), comp_v = reinterpret_cast<uint64_t>(comp_rec);
   int hist_last_v = kp.hist_bins - 1, hist_shift_v = kp.hist_shift, max_req_v = kp.max_requests;
@@ -210,6 +220,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   uint32_t rd_t = 1;   // reader cursor: slot ...
   int rd_k = 0;        // ... and arrivals of that slot already handed out
   int win = 0;         // lane i: n_t | B_t << 16 for the i-th slot of the current window
+  uint64_t cal = 0;    // bit i: some request may complete in the i-th slot of the current window
   // statistics: lane k of (acc_hi:acc_lo) is counter SL_k; lanes 0..2 of mx are max U, |P|, |Q|
   uint32_t acc_lo = 0, acc_hi = 0;
   int mx = 0;
@@ -218,19 +229,20 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   int lat_max = 0;
   int trace_left = kp.trace_every > 0 ? kp.trace_every : 0x7fffffff, trace_idx = 0;  // T < 2^30
 
-  auto fail = [&](int code, int t) __attribute__((always_inline)) {
-    if (!err) { err = code; err_step = t; }
-  };
+  // records the first error of the path (a macro: the error state must stay in registers)
+#define FCS_FAIL(code, tt) do { if (!err) { err = (code); err_step = (tt); } } while (0)
 
   // n_t and B_t of slot t0 + lane (Section 2.1: n_t from a known law with mean lambda;
   // Theorem 2: B_t i.i.d. bounded integers with mean b)
+  // the thresholds of the arrival law stay in lanes (at most kMaxCountThr of them)
+  const DLaw arr_law = laws[cellp.arrival];
+  const int arr_n = rfl(arr_law.n);
+  const int arr_thr_v = lane < arr_n ? static_cast<int>(kp.blob[arr_law.off + static_cast<uint32_t>(lane)]) : -1;
   auto draw_slot = [&](uint32_t t0, int& n_out, int& b_out) __attribute__((always_inline)) {
-    const DLaw arr = laws[cellp.arrival];
-    const uint32_t* __restrict__ arr_thr = kp.blob + arr.off;
     uint32_t w0, w1, w2, w3;
     philox4x32_10(0u, t0 + static_cast<uint32_t>(lane), rep, 0u, kp.seed_lo, kp.seed_hi, w0, w1, w2, w3);
     int n = 0;
-    for (int i = 0; i < arr.n; ++i) n += (w0 >= arr_thr[i]) ? 1 : 0;
+    for (int i = 0; i < arr_n; ++i) n += (w0 >= static_cast<uint32_t>(rdl(arr_thr_v, i))) ? 1 : 0;
     n_out = n;
     b_out = cellp.b_floor + ((w1 < cellp.b_frac_thr) ? 1 : 0);
   };
@@ -306,61 +318,57 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
     }
   };
 
-  // Order-preserving removal of dead slots.
-  auto compact = [&]() __attribute__((always_inline)) {
+  // Statistics of completed requests (Section 4: average and tail latency), taken in the lanes
+  // flagged `mine` from the record of the request and the slot `e` in which it completed.
+  auto account = [&](bool mine, v4i rec, int e) __attribute__((always_inline)) {
+    if (mine) {
+      const int lat = e - rec.z + 1;              // arrival to completion, both slots counted
+      const uint32_t s = lat_lo + static_cast<uint32_t>(lat);
+      lat_hi += (s < lat_lo) ? 1u : 0u;
+      lat_lo = s;
+      const uint32_t u = use_lo + static_cast<uint32_t>(rec.y);
+      use_hi += (u < use_lo) ? 1u : 0u;
+      use_lo = u;
+      lat_max = max(lat_max, lat);
+      if (hist_v) atomicAdd(reinterpret_cast<uint32_t*>(hist_v) + min(lat >> hist_shift_v, hist_last_v), 1u);
+      if (comp_v && rec.w < max_req_v) reinterpret_cast<int32_t*>(comp_v)[rec.w] = e;
+    }
+  };
+
+  // Order-preserving removal of dead slots; tlive is the first slot in which a decoding request
+  // that is still there generates a token (the current slot, or the next one once the
+  // completions of the current slot are done).  Requests that completed are accounted here.
+  auto compact = [&](int tlive) __attribute__((always_inline)) {
     int out = 0, new_pf = -1;
-    if (n_slots <= LC) {
-      for (int base = 0; base < n_slots; base += kWave) {
-        const int pos = base + lane;
-        const int rem = smem[pos], pl = smem[O_PL + pos];
-        const v4i rec = ld4(&smem[O_REC + 4 * pos]);
-        const bool live = pos < n_slots && (rem > 0 || pl > 0);
-        const uint64_t m = __ballot(live);
-        const uint64_t pm = __ballot(live && pl > 0);
-        const int dst = out + lanes_below(m);
-        if (pm != 0 && new_pf < 0) new_pf = out + __popcll(m & ((1ull << __builtin_ctzll(pm)) - 1ull));
-        wave_sync();
-        if (live) {
-          smem[dst] = rem;
-          smem[O_PL + dst] = pl;
-          st4(&smem[O_REC + 4 * dst], rec);
+    for (int base = 0; base < n_slots; base += kWave) {
+      const int pos = base + lane;
+      const bool in = pos < n_slots;
+      int end = -1, pl = 0;
+      v4i rec = {0, 0, 0, 0};
+      if (in) {
+        if (LIKELY(base < LC)) {
+          end = smem[2 * pos]; pl = smem[O_PL + pos];
+          rec = ld4(&smem[O_REC + 4 * pos]);
+        } else {
+          end = hREM[pos - LC]; pl = hPL[pos - LC];
+          rec = ld4(&hREC[4 * static_cast<size_t>(pos - LC)]);
         }
-        wave_sync();
-        out += __popcll(m);
       }
-      for (int base = out; base < n_slots; base += kWave) {
-        const int pos = base + lane;
-        if (pos < n_slots) { smem[pos] = -1; smem[O_PL + pos] = 0; }
-      }
-    } else {
-      for (int base = 0; base < n_slots; base += kWave) {
-        const int pos = base + lane;
-        const bool in = pos < n_slots;
-        int rem = -1, pl = 0;
-        v4i rec = {0, 0, 0, 0};
-        if (in) {
-          if (base < LC) {
-            rem = smem[pos]; pl = smem[O_PL + pos];
-            rec = ld4(&smem[O_REC + 4 * pos]);
-          } else {
-            rem = hREM[pos - LC]; pl = hPL[pos - LC];
-            rec = ld4(&hREC[4 * static_cast<size_t>(pos - LC)]);
-          }
-        }
-        const bool live = in && (rem > 0 || pl > 0);
-        const uint64_t m = __ballot(live);
-        const uint64_t pm = __ballot(live && pl > 0);
-        const int dst = out + lanes_below(m);
-        if (pm != 0 && new_pf < 0) new_pf = out + __popcll(m & ((1ull << __builtin_ctzll(pm)) - 1ull));
-        wave_sync();
-        if (live) slot_store(dst, rem, pl, rec);
-        wave_sync();
-        out += __popcll(m);
-      }
-      for (int base = out; base < n_slots; base += kWave) {
-        const int pos = base + lane;
-        if (pos < n_slots) rem_pl_store(pos, -1, 0);
-      }
+      const bool pf = in && end < 0 && pl > 0;
+      const bool live = pf || (in && end >= tlive);
+      account(in && end >= 0 && end < tlive, rec, end);
+      const uint64_t m = __ballot(live);
+      const uint64_t pm = __ballot(pf);
+      const int dst = out + lanes_below(m);
+      if (pm != 0 && new_pf < 0) new_pf = out + __popcll(m & ((1ull << __builtin_ctzll(pm)) - 1ull));
+      wave_sync();
+      if (live) slot_store(dst, end, pf ? pl : 0, rec);
+      wave_sync();
+      out += __popcll(m);
+    }
+    for (int base = out; base < n_slots; base += kWave) {
+      const int pos = base + lane;
+      if (pos < n_slots) end_pl_store(pos, -1, 0);
     }
     wave_sync();
     n_slots = out;
@@ -371,24 +379,33 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   // its progress and goes back to the front of Q.
   auto evict_newest = [&](int t) __attribute__((always_inline)) {
     int pos = n_slots - 1;
-    int rem = 0, pleft = 0;
+    int end = 0, pleft = 0;
     for (; pos >= 0; --pos) {
-      rem_pl_load(pos, rem, pleft);
-      rem = rfl(rem);
+      end_pl_load(pos, end, pleft);
+      end = rfl(end);
       pleft = rfl(pleft);
-      if (rem > 0 || pleft > 0) break;
+      if (end >= t || (end < 0 && pleft > 0)) break;
+      if (end >= 0) {  // a request that completed: its slot goes away here, so account it here
+        account(lane == 0, rec_load(pos), end);
+        if (lane == 0) end_pl_store(pos, -1, 0);
+      }
     }
-    if (pos < 0) { fail(FCS_ESTATE, t); return; }
+    if (pos < 0) { FCS_FAIL(FCS_ESTATE, t); return; }
     const v4i rec = rec_load(pos);
     const int l = rfl(rec.x), o = rfl(rec.y);
-    if (pleft > 0) { U -= l; n_pf -= 1; }
-    else { U -= l + (o - rem); n_dec -= 1; }
+    // a decoding request had end - t + 1 of its o tokens still to come (written without branches:
+    // two branches that each decrement a counter get merged into a store through a selected
+    // pointer, which forces both counters out of registers)
+    const int pf = end < 0 ? 1 : 0;
+    U -= l + (pf ? 0 : o - (end - t + 1));
+    n_pf -= pf;
+    n_dec -= 1 - pf;
     n_live -= 1;
-    if (sdepth == SCAP) { fail(FCS_EOVERFLOW, t); return; }
+    if (sdepth == SCAP) { FCS_FAIL(FCS_EOVERFLOW, t); return; }
     if (lane == 0) {
       if (sdepth < kStackLds) st4(&smem[O_STK + 4 * sdepth], rec);
       else st4(&hSTK[4 * static_cast<size_t>(sdepth - kStackLds)], rec);
-      rem_pl_store(pos, -1, 0);
+      end_pl_store(pos, -1, 0);
     }
     wave_sync();
     sdepth += 1;
@@ -409,25 +426,17 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   int room = 0, admitted = 0, budget = 0, new_dec = 0;
   int rel_sum = 0, n_done = 0;  // completions of this slot: released footprint and count
 
-  // called where the lanes of mask m0 (flag `mine`) own a request, in slot `pos`, that generated
-  // its last token in this slot
+  // called where the lanes of mask m0 (flag `mine`) hold a request, in slot `pos`, that generates
+  // its last token in this slot: counts it and adds its footprint l + o to what the slot releases
   auto complete = [&](bool mine, uint64_t m0, int pos) __attribute__((always_inline)) {
     int relv = 0;
     if (mine) {
-      v4i rec;
-      if (LIKELY(pos < LC)) rec = ld4(&smem[O_REC + 4 * pos]);
-      else rec = ld4(&hREC[4 * static_cast<size_t>(pos - LC)]);
-      relv = rec.x + rec.y;                       // l + o, released at the end of the slot
-      const int lat = t - rec.z + 1;              // arrival to completion, both slots counted
-      const uint32_t s = lat_lo + static_cast<uint32_t>(lat);
-      lat_hi += (s < lat_lo) ? 1u : 0u;
-      lat_lo = s;
-      const uint32_t u = use_lo + static_cast<uint32_t>(rec.y);
-      use_hi += (u < use_lo) ? 1u : 0u;
-      use_lo = u;
-      lat_max = max(lat_max, lat);
-      if (hist_v) atomicAdd(reinterpret_cast<uint32_t*>(hist_v) + min(lat >> hist_shift_v, hist_last_v), 1u);
-      if (comp_v && rec.w < max_req_v) reinterpret_cast<int32_t*>(comp_v)[rec.w] = t;
+      if (LIKELY(pos < LC)) {
+        relv = smem[2 * pos + 1];
+      } else {
+        const v4i rec = ld4(&hREC[4 * static_cast<size_t>(pos - LC)]);
+        relv = rec.x + rec.y;
+      }
     }
     n_done += static_cast<int>(__popcll(m0));
     rel_sum += rdl(relv, __builtin_ctzll(m0));
@@ -435,24 +444,6 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
     while (UNLIKELY(m != 0)) {
       rel_sum += rdl(relv, __builtin_ctzll(m));
       m &= m - 1;
-    }
-  };
-  // completes every request of a four-slots-per-lane block whose entry reached zero and turns
-  // the entry into a tombstone
-  auto complete_block = [&](v4i& v, int p0) __attribute__((always_inline)) {
-    bool any = umin4(v) == 0u;
-    uint64_t m = __ballot(any);
-    while (m != 0) {  // one pass unless a lane holds two completions
-      const int c = v.x == 0 ? 0 : (v.y == 0 ? 1 : (v.z == 0 ? 2 : 3));
-      complete(any, m, p0 + c);
-      if (any) {
-        v.x = c == 0 ? -1 : v.x;
-        v.y = c == 1 ? -1 : v.y;
-        v.z = c == 2 ? -1 : v.z;
-        v.w = c == 3 ? -1 : v.w;
-      }
-      any = umin4(v) == 0u;
-      m = __ballot(any);
     }
   };
   // step 5 (Section 2.1: U_t after processing, before completed requests leave) and step 6
@@ -482,6 +473,26 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
     n_dec -= n_done;
   };
 
+  // Bit i is set when some END entry equals t0 + i (t0 = first slot of a window).
+  auto calendar_of_window = [&](int t0) __attribute__((always_inline)) -> uint64_t {
+    uint32_t lo = 0, hi = 0;
+    for (int base = 0; base < n_slots; base += kWave) {
+      const int pos = base + lane;
+      int v = -1;
+      if (pos < n_slots) v = LIKELY(base < LC) ? smem[2 * pos] : hREM[pos - LC];
+      const uint32_t d = static_cast<uint32_t>(v - t0);
+      lo |= d < 32u ? 1u << d : 0u;
+      hi |= (d >= 32u && d < 64u) ? 1u << (d - 32u) : 0u;
+    }
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) {
+      lo |= static_cast<uint32_t>(__shfl_xor(static_cast<int>(lo), d, kWave));
+      hi |= static_cast<uint32_t>(__shfl_xor(static_cast<int>(hi), d, kWave));
+    }
+    return (static_cast<uint64_t>(static_cast<uint32_t>(rfl(static_cast<int>(hi)))) << 32) |
+           static_cast<uint32_t>(rfl(static_cast<int>(lo)));
+  };
+
   auto general_slot = [&]() __attribute__((always_inline)) {
     // ---- 1. arrivals ---------------------------------------------------------------
     if (phase <= 0) {
@@ -491,7 +502,8 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
         int n, b;
         draw_slot(static_cast<uint32_t>(t), n, b);
         win = n | (b << 16);
-        if (UNLIKELY(arrived >= 0x7ffe0000u)) fail(FCS_EOVERFLOW, t);
+        cal = calendar_of_window(t);
+        if (UNLIKELY(arrived >= 0x7ffe0000u)) FCS_FAIL(FCS_EOVERFLOW, t);
         if (arr_rec) {  // arrival slots of the requests of this window, by arrival id
           const int tt = t + lane;
           const int ne = tt <= T ? n : 0;
@@ -517,7 +529,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
         if (!from_stack) {
           if (UNLIKELY(static_cast<int>(fresh_next - fb_base) >= fb_count)) refill_block();
           idx = static_cast<int>(fresh_next - fb_base);
-          if (UNLIKELY(idx >= fb_count)) { fail(FCS_ESTATE, t); break; }
+          if (UNLIKELY(idx >= fb_count)) { FCS_FAIL(FCS_ESTATE, t); break; }
         }
         if (greedy) {
           if (head_l < 0) {
@@ -531,8 +543,8 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
           if (U + n_live + head_l + 1 > M) break;
         }
         if (UNLIKELY(n_slots == CAP)) {
-          if (n_live < n_slots) compact();
-          if (n_slots == CAP) { fail(FCS_EOVERFLOW, t); break; }
+          if (n_live < n_slots) compact(t);
+          if (n_slots == CAP) { FCS_FAIL(FCS_EOVERFLOW, t); break; }
         }
         const int pos = n_slots;
         int l;
@@ -542,13 +554,13 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
           if (d < kStackLds) rec = ld4(&smem[O_STK + 4 * d]);
           else rec = ld4(&hSTK[4 * static_cast<size_t>(d - kStackLds)]);
           l = rfl(rec.x);
-          if (lane == 0) slot_store(pos, -rec.y, l, rec);
+          if (lane == 0) slot_admit(pos, l, rec);
           sdepth = d;
         } else {
           l = rdl(fb_l, idx);
           if (lane == idx) {
             const v4i rec = {fb_l, fb_o, fb_t, static_cast<int>(fresh_next)};
-            slot_store(pos, -fb_o, fb_l, rec);
+            slot_admit(pos, fb_l, rec);
           }
           fresh_next += 1u;
         }
@@ -584,11 +596,15 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
         int first_left = -1;
         while (todo > 0 && budget > 0 && base < n_slots) {
           const int pos = base + lane;
-          int pl, ov;
-          if (LIKELY(base < LC)) { pl = smem[O_PL + pos]; ov = smem[O_REC + 4 * pos + 1]; }
-          else if (pos < n_slots) { pl = hPL[pos - LC]; ov = hREC[4 * static_cast<size_t>(pos - LC) + 1]; }
-          else { pl = 0; ov = 0; }
-          uint64_t m = __ballot(pl > 0);
+          int pl = 0, lv = 0, ov = 0, e = 0;
+          if (LIKELY(base < LC)) {
+            pl = smem[O_PL + pos]; e = smem[2 * pos];
+            lv = smem[O_REC + 4 * pos]; ov = smem[O_REC + 4 * pos + 1];
+          } else if (pos < n_slots) {
+            pl = hPL[pos - LC]; e = hREM[pos - LC];
+            lv = hREC[4 * static_cast<size_t>(pos - LC)]; ov = hREC[4 * static_cast<size_t>(pos - LC) + 1];
+          }
+          uint64_t m = __ballot(e < 0 && pl > 0);
           while (m != 0 && budget > 0) {
             const int i = __builtin_ctzll(m);
             m &= m - 1;
@@ -599,10 +615,16 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
             budget -= d;
             todo -= 1;
             if (left == 0) {
-              // the chunk that ends the prompt yields token 1: the entry becomes o here and the
-              // decode pass of this slot makes it o - 1
+              // the chunk that ends the prompt yields token 1 in this slot, so token o comes in
+              // slot t + o - 1 (this very slot when o = 1)
               const int o = rdl(ov, i);
-              if (lane == 0) rem_pl_store(p, o, 0);
+              const int foot = rdl(lv, i) + o;
+              if (lane == 0) {
+                if (LIKELY(p < LC)) { smem[2 * p] = t + o - 1; smem[2 * p + 1] = foot; smem[O_PL + p] = 0; }
+                else { hREM[p - LC] = t + o - 1; hPL[p - LC] = 0; }
+              }
+              const int k = ((t - 1) & (kWave - 1)) + o - 1;
+              if (k < kWave) cal |= 1ull << k;
               new_dec += 1;
             } else {
               if (lane == 0) {
@@ -632,30 +654,34 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
       n_done = 0;
       int advanced;  // requests already decoding that got a token
       if (LIKELY(budget >= n_dec)) {
+        // every decoding request gets its token; only the ones whose last token this is need a look
         advanced = n_dec;
-        const int lim = min(n_slots, LC);
-        for (int b0 = 0; b0 < lim; b0 += kLdsBlock) {
-          const int p0 = b0 + (lane << 2);
-          v4i v = ld4(&smem[p0]);
-          dec4(v);
-          if (__ballot(umin4(v) == 0u) != 0) complete_block(v, p0);
-          st4(&smem[p0], v);
-          wave_sync();
-        }
-        for (int base = LC; base < n_slots; base += kWave) {
-          const int pos = base + lane;
-          const bool in = pos < n_slots;
-          int v = in ? hREM[pos - LC] : -1;
-          v -= (v > 0) ? 1 : 0;
-          const bool d = in && v == 0;
-          const uint64_t dm = __ballot(d);
-          if (dm != 0) complete(d, dm, pos);
-          if (in) hREM[pos - LC] = d ? -1 : v;
-          wave_sync();
+        if ((cal >> ((t - 1) & (kWave - 1))) & 1ull) {
+          const int lim = min(n_slots, LC);
+          for (int b0 = 0; b0 < lim; b0 += kLdsBlock) {  // four {END, FOOT} pairs per lane
+            const int p0 = b0 + (lane << 2);
+            const v4i a = ld4(&smem[2 * p0]), b = ld4(&smem[2 * p0 + 4]);
+            const int cnt = (a.x == t ? 1 : 0) + (a.z == t ? 1 : 0) + (b.x == t ? 1 : 0) + (b.z == t ? 1 : 0);
+            const int relv = (a.x == t ? a.y : 0) + (a.z == t ? a.w : 0) + (b.x == t ? b.y : 0) + (b.z == t ? b.w : 0);
+            uint64_t m = __ballot(cnt != 0);
+            while (m != 0) {
+              const int i = __builtin_ctzll(m);
+              m &= m - 1;
+              n_done += rdl(cnt, i);
+              rel_sum += rdl(relv, i);
+            }
+          }
+          for (int base = LC; base < n_slots; base += kWave) {
+            const int pos = base + lane;
+            const bool d = pos < n_slots && hREM[pos - LC] == t;
+            const uint64_t dm = __ballot(d);
+            if (dm != 0) complete(d, dm, pos);
+          }
         }
       } else {
-        // budget binds: the first `budget` already-decoding requests in activation order advance;
-        // requests that finished their prompt in this slot (entry == o) take token 1 for free
+        // budget binds: the first `budget` already-decoding requests in activation order advance
+        // and the others finish one slot later; requests that finished their prompt in this slot
+        // (all o tokens still to come) take token 1 for free
         int left = budget;
         advanced = 0;
         for (int base = 0; base < n_slots; base += kWave) {
@@ -663,31 +689,31 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
           const bool in = pos < n_slots;
           int v = -1, ov = 0;
           if (in) {
-            if (base < LC) { v = smem[pos]; ov = smem[O_REC + 4 * pos + 1]; }
+            if (base < LC) { v = smem[2 * pos]; ov = smem[O_REC + 4 * pos + 1]; }
             else { v = hREM[pos - LC]; ov = hREC[4 * static_cast<size_t>(pos - LC) + 1]; }
           }
-          const bool dec = v > 0;
-          const bool fresh = dec && new_dec > 0 && v == ov;
+          const bool dec = v >= t;
+          const bool fresh = dec && new_dec > 0 && v - t + 1 == ov;
           const bool old = dec && !fresh;
           const uint64_t om = __ballot(old);
           const bool go = fresh || (old && lanes_below(om) < left);
           const int took = min(static_cast<int>(__popcll(om)), left);
           left -= took;
           advanced += took;
-          if (go) v -= 1;
-          const bool d = go && v == 0;
+          const bool d = go && v == t;
           const uint64_t dm = __ballot(d);
           if (dm != 0) complete(d, dm, pos);
-          if (go) {
-            if (base < LC) smem[pos] = d ? -1 : v; else hREM[pos - LC] = d ? -1 : v;
+          if (old && !go) {
+            if (base < LC) smem[2 * pos] = v + 1; else hREM[pos - LC] = v + 1;
           }
           wave_sync();
         }
+        cal |= cal << 1;  // a stalled request moved to the next slot: keep the calendar a superset
         x = wrl(n_dec - advanced, SL_STALLED, x);
       }
       measure_and_release(advanced + new_dec, qlen);
     }
-    if (n_slots - n_live >= kCompactSlack) compact();
+    if (n_slots - n_live >= kCompactSlack) compact(t + 1);
   };
 
   // The common slot (everything in LDS, no eviction, no stall) as hand-scheduled assembly; runs
@@ -698,12 +724,14 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
 #include "fcs_fast_slots.inc"
   };
 
-  const bool fast_ok = LC >= 2 * kLdsBlock;
+  // its 32-bit sums over up to 64 slots need U and |Q| below 2^25
+  const bool fast_ok = LC >= 2 * kLdsBlock && M < (1 << 25);
   while (t <= T && !err) {
     general_slot();
     ++t;
     phase = 0;
     if (UNLIKELY(!fast_ok) || UNLIKELY(n_slots > LC) || UNLIKELY(err)) continue;
+    if (UNLIKELY(arrived - fresh_next >= (1u << 25))) continue;
     fast_slots();
   }
 
@@ -711,17 +739,17 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   uint64_t h = 14695981039346656037ull;
   auto mix = [&](uint64_t w) __attribute__((always_inline)) { h = (h ^ w) * 1099511628211ull; };
   if (!err) {
-    compact();
+    compact(t);  // t = T + 1 here
     mix(static_cast<uint64_t>(n_slots));
     for (int pos = 0; pos < n_slots; ++pos) {
       int rem, pleft;
-      rem_pl_load(pos, rem, pleft);
+      end_pl_load(pos, rem, pleft);
       rem = rfl(rem);
-      pleft = rfl(pleft);
+      pleft = rem < 0 ? rfl(pleft) : 0;
       const v4i rec = rec_load(pos);
       const int l = rfl(rec.x), o = rfl(rec.y), id = rfl(rec.w);
       mix(static_cast<uint64_t>(id));
-      mix(static_cast<uint64_t>(rem > 0 ? o - rem : 0));
+      mix(static_cast<uint64_t>(rem > T ? o - (rem - T) : 0));  // rem - T tokens still to come
       mix(static_cast<uint64_t>(l - pleft));
     }
     mix(static_cast<uint64_t>(sdepth));
