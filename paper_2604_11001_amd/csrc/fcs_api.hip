@@ -179,9 +179,11 @@ static int geometry_for(fcs_engine* h, int64_t n_replicas, int32_t* lcap, int32_
   int32_t lc = h->lds_slots_param;
   if (lc == 0) {
     // spread the paths over the 256 compute units and give each wavefront an equal share of
-    // the 160 KB of LDS, between 4 and 12 wavefronts per unit
+    // the 160 KB of LDS, between 4 and 8 wavefronts per unit (8 leaves 512 slots, which the
+    // hand-scheduled slot loop of the kernel needs; a path is a latency chain, so more resident
+    // wavefronts per unit buy less than running each of them in that loop)
     int64_t per_cu = (n_paths + 255) / 256;
-    per_cu = std::min<int64_t>(std::max<int64_t>(per_cu, 4), 12);
+    per_cu = std::min<int64_t>(std::max<int64_t>(per_cu, 4), 8);
     const int64_t words = (160 * 1024 / per_cu) / 4 - S_NFIELDS * kStackLds - kScratchWords;
     lc = static_cast<int32_t>(words / kLdsWordsPerSlot / kLdsBlock * kLdsBlock);
     lc = std::min(std::max(lc, kLdsBlock), 2048);

@@ -130,3 +130,57 @@ def test_config4_scaled_with_and_without_spill():
     wl = configs.config4(oracle.stability_bound).scaled(n_replicas=6, n_steps=40000)
     compare(run(wl), wl, replica_ids=[0, 3], label="cfg4 scaled")
     compare(run(wl, lds_slots=256), wl, replica_ids=[0, 3], label="cfg4 scaled, small LDS tile")
+
+
+# ---- the configurations at their full sizes, in the launch geometry the benchmark uses ----------------
+# The oracle follows a few sampled paths of each; over all paths the identities that hold at any size are
+# checked: every arrival is completed, active or waiting; every activation is completed, active or evicted.
+
+def _full_size(wl, samples, label, n_threads=16):
+    eng = run(wl.scaled(max_requests=0))
+    got, _, _ = compare(eng, wl, replica_ids=samples, n_threads=n_threads, label=label)
+    a = {k: v.astype(np.int64) for k, v in got.items()}
+    assert np.array_equal(a["arrived"], a["completed"] + a["final_p"] + a["final_q"]), label
+    assert np.array_equal(a["activations"], a["completed"] + a["final_p"] + a["evictions"]), label
+    assert np.all(a["max_u"] <= wl.capacity) and np.all(a["sum_u"] <= a["max_u"] * eng.n_steps), label
+    return eng, got
+
+
+def test_config1_full_size_sampled_paths():
+    wl = configs.config1(oracle.stability_bound)
+    eng, got = _full_size(wl, [0, 417, 1023], "cfg1 full")
+    R = eng.n_replicas
+    assert eng.n_paths == 2048 and eng.n_steps == 100000
+    assert np.array_equal(got["arrived"][:R], got["arrived"][R:])   # both policies see the same arrivals
+
+
+def test_config2_full_size_sampled_paths():
+    wl = configs.config2(oracle.stability_bound)
+    eng, _ = _full_size(wl, [0, 4095], "cfg2 full")
+    assert eng.n_paths == 12288 and eng.n_steps == 200000
+
+
+def test_config3_full_size_sampled_paths():
+    wl = configs.config3(oracle.stability_bound)
+    eng = run(wl)
+    assert eng.n_paths == 262144 and eng.n_steps == 50000
+    got, _ = eng.stats()
+    assert not np.any(got["error"])
+    R = eng.n_replicas
+    hist = eng.hist.cpu().numpy().view(np.uint32)
+    for ci in (0, 777, 2047):            # corners and one interior point of the (lambda, b) grid
+        ids = np.array([0, R - 1])
+        ref = oracle.run_cell(wl, ci, replica_ids=ids, n_threads=16)
+        rows = ci * R + ids
+        for name in oracle.counter_names():
+            assert np.array_equal(ref["counters"][name], got[name][rows]), (ci, name)
+        assert np.array_equal(ref["hist"], hist[rows]), (ci, "hist")
+    a = {k: v.astype(np.int64) for k, v in got.items()}
+    assert np.array_equal(a["arrived"], a["completed"] + a["final_p"] + a["final_q"])
+    assert np.array_equal(a["activations"], a["completed"] + a["final_p"] + a["evictions"])
+
+
+def test_config4_full_size_sampled_paths():
+    wl = configs.config4(oracle.stability_bound)
+    eng, _ = _full_size(wl, [0, 511], "cfg4 full")
+    assert eng.n_paths == 512 and eng.n_steps == 1000000
