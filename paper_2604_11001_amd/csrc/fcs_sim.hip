@@ -80,22 +80,43 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__device__ __forceinline__ int wave_incl_sum(int v, int lane) {
-#pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) {
-    const int o = __shfl_up(v, d, kWave);
-    if (lane >= d) v += o;
-  }
+// Wavefront scans and reductions of non-negative values with DPP (row shifts inside the rows of 16
+// lanes, then the last lane of a row broadcast to the rows after it); zero is the fill value and the
+// identity of all three operations.
+#define FCS_DPP(v, ctrl, row_mask) __builtin_amdgcn_update_dpp(0, (v), (ctrl), (row_mask), 0xf, false)
+enum { DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR4 = 0x114, DPP_ROW_SHR8 = 0x118,
+       DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143 };
+
+__device__ __forceinline__ int wave_incl_sum(int v) {
+  v += FCS_DPP(v, DPP_ROW_SHR1, 0xf);
+  v += FCS_DPP(v, DPP_ROW_SHR2, 0xf);
+  v += FCS_DPP(v, DPP_ROW_SHR4, 0xf);
+  v += FCS_DPP(v, DPP_ROW_SHR8, 0xf);
+  v += FCS_DPP(v, DPP_ROW_BCAST15, 0xa);
+  v += FCS_DPP(v, DPP_ROW_BCAST31, 0xc);
   return v;
 }
 
-__device__ __forceinline__ int wave_incl_max(int v, int lane) {
-#pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) {
-    const int o = __shfl_up(v, d, kWave);
-    if (lane >= d) v = max(v, o);
-  }
+__device__ __forceinline__ int wave_incl_max(int v) {
+  v = max(v, FCS_DPP(v, DPP_ROW_SHR1, 0xf));
+  v = max(v, FCS_DPP(v, DPP_ROW_SHR2, 0xf));
+  v = max(v, FCS_DPP(v, DPP_ROW_SHR4, 0xf));
+  v = max(v, FCS_DPP(v, DPP_ROW_SHR8, 0xf));
+  v = max(v, FCS_DPP(v, DPP_ROW_BCAST15, 0xa));
+  v = max(v, FCS_DPP(v, DPP_ROW_BCAST31, 0xc));
   return v;
+}
+
+// OR over the wavefront, valid in lane 63 (returned from there)
+__device__ __forceinline__ uint32_t wave_or(uint32_t u) {
+  int v = static_cast<int>(u);
+  v |= FCS_DPP(v, DPP_ROW_SHR1, 0xf);
+  v |= FCS_DPP(v, DPP_ROW_SHR2, 0xf);
+  v |= FCS_DPP(v, DPP_ROW_SHR4, 0xf);
+  v |= FCS_DPP(v, DPP_ROW_SHR8, 0xf);
+  v |= FCS_DPP(v, DPP_ROW_BCAST15, 0xa);
+  v |= FCS_DPP(v, DPP_ROW_BCAST31, 0xc);
+  return static_cast<uint32_t>(__builtin_amdgcn_readlane(v, kWave - 1));
 }
 
 __device__ __forceinline__ int lanes_below(uint64_t mask) {
@@ -220,7 +241,9 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   uint32_t rd_t = 1;   // reader cursor: slot ...
   int rd_k = 0;        // ... and arrivals of that slot already handed out
   int win = 0;         // lane i: n_t | B_t << 16 for the i-th slot of the current window
-  uint64_t cal = 0;    // bit i: some request may complete in the i-th slot of the current window
+  // calendars: bit i = some request may complete in the i-th slot of the current window; cal0 for
+  // the requests in slots 0..255, cal1 for the others
+  uint64_t cal0 = 0, cal1 = 0;
   // statistics: lane k of (acc_hi:acc_lo) is counter SL_k; lanes 0..2 of mx are max U, |P|, |Q|
   uint32_t acc_lo = 0, acc_hi = 0;
   int mx = 0;
@@ -244,7 +267,8 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
     int n = 0;
     for (int i = 0; i < arr_n; ++i) n += (w0 >= static_cast<uint32_t>(rdl(arr_thr_v, i))) ? 1 : 0;
     n_out = n;
-    b_out = cellp.b_floor + ((w1 < cellp.b_frac_thr) ? 1 : 0);
+    // GREEDY is the limit of an unbounded B_t (remark after Theorem 2); 0x7fff exceeds any active set
+    b_out = greedy ? 0x7fff : cellp.b_floor + ((w1 < cellp.b_frac_thr) ? 1 : 0);
   };
 
   // Generates the next block of never-activated requests, in arrival order, starting at
@@ -257,7 +281,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
       draw_slot(rd_t, n, b);
       if (rd_t + static_cast<uint32_t>(lane) > static_cast<uint32_t>(T)) n = 0;
       if (lane == 0) n -= rd_k;
-      const int incl = wave_incl_sum(n, lane);
+      const int incl = wave_incl_sum(n);
       const int total = rdl(incl, kWave - 1);
       const int excl = incl - n;
       if (total == 0) { rd_t += kWave; rd_k = 0; continue; }
@@ -270,7 +294,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
       wave_sync();
       const int cnt = min(total, kWave);
       const bool valid = lane < cnt;
-      const int owner = wave_incl_max(mark, lane);
+      const int owner = wave_incl_max(mark);
       const int src = valid ? owner - 1 : 0;
       const int ex_s = __shfl(excl, src, kWave);
       const int k = lane - ex_s + (src == 0 ? rd_k : 0);
@@ -373,6 +397,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
     wave_sync();
     n_slots = out;
     pf_first = new_pf < 0 ? n_slots : new_pf;
+    cal0 |= cal1;  // requests moved towards slot 0
   };
 
   // Evicts the most recently activated request (Section 3.3: last in, first out); it loses
@@ -422,6 +447,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   // has reached.  Variables of the slot in flight are shared between the two.
   int t = 1;
   int phase = 0;  // 0 slot start, 1 admission, 3 overflow check, 4 decode pass, 6 compaction only
+  int resume = 0; // 1: the hand-scheduled loop takes the slot in flight up again at its admission step
   int x = 0;      // this slot's contribution to the statistics, one counter per lane
   int room = 0, admitted = 0, budget = 0, new_dec = 0;
   int rel_sum = 0, n_done = 0;  // completions of this slot: released footprint and count
@@ -473,24 +499,40 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
     n_dec -= n_done;
   };
 
-  // Bit i is set when some END entry equals t0 + i (t0 = first slot of a window).
-  auto calendar_of_window = [&](int t0) __attribute__((always_inline)) -> uint64_t {
-    uint32_t lo = 0, hi = 0;
+  // Rebuilds the calendars of the window that starts at slot t0 from the END entries.
+  auto calendars_of_window = [&](int t0) __attribute__((always_inline)) {
+    uint32_t lo0 = 0, hi0 = 0, lo1 = 0, hi1 = 0;
     for (int base = 0; base < n_slots; base += kWave) {
       const int pos = base + lane;
       int v = -1;
       if (pos < n_slots) v = LIKELY(base < LC) ? smem[2 * pos] : hREM[pos - LC];
       const uint32_t d = static_cast<uint32_t>(v - t0);
-      lo |= d < 32u ? 1u << d : 0u;
-      hi |= (d >= 32u && d < 64u) ? 1u << (d - 32u) : 0u;
+      const uint32_t lo = d < 32u ? 1u << d : 0u;
+      const uint32_t hi = (d >= 32u && d < 64u) ? 1u << (d - 32u) : 0u;
+      if (base < kLdsBlock) { lo0 |= lo; hi0 |= hi; } else { lo1 |= lo; hi1 |= hi; }
     }
-#pragma unroll
-    for (int d = kWave / 2; d > 0; d >>= 1) {
-      lo |= static_cast<uint32_t>(__shfl_xor(static_cast<int>(lo), d, kWave));
-      hi |= static_cast<uint32_t>(__shfl_xor(static_cast<int>(hi), d, kWave));
+    cal0 = (static_cast<uint64_t>(wave_or(hi0)) << 32) | wave_or(lo0);
+    cal1 = (static_cast<uint64_t>(wave_or(hi1)) << 32) | wave_or(lo1);
+  };
+
+  // First slot t0 of a 64-slot window: draws n_t and B_t of the window and rebuilds the calendar.
+  int win_t0 = 0;
+  auto window_start = [&](int t0) __attribute__((always_inline)) {
+    int n, b;
+    draw_slot(static_cast<uint32_t>(t0), n, b);
+    win = n | (b << 16);
+    calendars_of_window(t0);
+    win_t0 = t0;
+    if (UNLIKELY(arrived >= 0x7ffe0000u)) FCS_FAIL(FCS_EOVERFLOW, t0);
+    if (arr_rec) {  // arrival slots of the requests of this window, by arrival id
+      const int tt = t0 + lane;
+      const int ne = tt <= T ? n : 0;
+      const int excl = wave_incl_sum(ne) - ne;
+      for (int k = 0; k < ne; ++k) {
+        const uint32_t id = arrived + static_cast<uint32_t>(excl + k);
+        if (id < static_cast<uint32_t>(kp.max_requests)) arr_rec[id] = tt;
+      }
     }
-    return (static_cast<uint64_t>(static_cast<uint32_t>(rfl(static_cast<int>(hi)))) << 32) |
-           static_cast<uint32_t>(rfl(static_cast<int>(lo)));
   };
 
   auto general_slot = [&]() __attribute__((always_inline)) {
@@ -498,22 +540,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
     if (phase <= 0) {
       x = 0;
       const int wi = (t - 1) & (kWave - 1);
-      if (wi == 0) {
-        int n, b;
-        draw_slot(static_cast<uint32_t>(t), n, b);
-        win = n | (b << 16);
-        cal = calendar_of_window(t);
-        if (UNLIKELY(arrived >= 0x7ffe0000u)) FCS_FAIL(FCS_EOVERFLOW, t);
-        if (arr_rec) {  // arrival slots of the requests of this window, by arrival id
-          const int tt = t + lane;
-          const int ne = tt <= T ? n : 0;
-          const int excl = wave_incl_sum(ne, lane) - ne;
-          for (int k = 0; k < ne; ++k) {
-            const uint32_t id = arrived + static_cast<uint32_t>(excl + k);
-            if (id < static_cast<uint32_t>(kp.max_requests)) arr_rec[id] = tt;
-          }
-        }
-      }
+      if (wi == 0 && win_t0 != t) window_start(t);
       const int nb = rdl(win, wi);
       arrived += static_cast<uint32_t>(nb & 0xffff);
       const int ql = sdepth + static_cast<int>(arrived - fresh_next);
@@ -624,7 +651,9 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
                 else { hREM[p - LC] = t + o - 1; hPL[p - LC] = 0; }
               }
               const int k = ((t - 1) & (kWave - 1)) + o - 1;
-              if (k < kWave) cal |= 1ull << k;
+              if (k < kWave) {
+                if (p < kLdsBlock) cal0 |= 1ull << k; else cal1 |= 1ull << k;
+              }
               new_dec += 1;
             } else {
               if (lane == 0) {
@@ -656,7 +685,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
       if (LIKELY(budget >= n_dec)) {
         // every decoding request gets its token; only the ones whose last token this is need a look
         advanced = n_dec;
-        if ((cal >> ((t - 1) & (kWave - 1))) & 1ull) {
+        if (((cal0 | cal1) >> ((t - 1) & (kWave - 1))) & 1ull) {
           const int lim = min(n_slots, LC);
           for (int b0 = 0; b0 < lim; b0 += kLdsBlock) {  // four {END, FOOT} pairs per lane
             const int p0 = b0 + (lane << 2);
@@ -708,7 +737,9 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
           }
           wave_sync();
         }
-        cal |= cal << 1;  // a stalled request moved to the next slot: keep the calendar a superset
+        // a stalled request moved to the next slot: keep the calendars supersets
+        cal0 |= cal0 << 1;
+        cal1 |= cal1 << 1;
         x = wrl(n_dec - advanced, SL_STALLED, x);
       }
       measure_and_release(advanced + new_dec, qlen);
@@ -727,12 +758,25 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   // its 32-bit sums over up to 64 slots need U and |Q| below 2^25
   const bool fast_ok = LC >= 2 * kLdsBlock && M < (1 << 25);
   while (t <= T && !err) {
+    if (LIKELY(fast_ok) && LIKELY(n_slots <= LC) && LIKELY(arrived - fresh_next < (1u << 25))) {
+      if (!resume && ((t - 1) & (kWave - 1)) == 0 && win_t0 != t) {
+        window_start(t);
+        if (UNLIKELY(err)) break;
+      }
+      fast_slots();
+      resume = 0;
+      if (t > T) break;
+      // a new window: draw it and go on in the loop
+      if (phase == 0 && ((t - 1) & (kWave - 1)) == 0 && win_t0 != t) continue;
+      // the block of fresh requests ran out in the middle of an admission: refill it and go on
+      if (phase == 1 && sdepth == 0 && n_slots < LC && static_cast<int>(fresh_next - fb_base) >= fb_count) {
+        refill_block();
+        if (LIKELY(static_cast<int>(fresh_next - fb_base) < fb_count)) { resume = 1; continue; }
+      }
+    }
     general_slot();
     ++t;
     phase = 0;
-    if (UNLIKELY(!fast_ok) || UNLIKELY(n_slots > LC) || UNLIKELY(err)) continue;
-    if (UNLIKELY(arrived - fresh_next >= (1u << 25))) continue;
-    fast_slots();
   }
 
   // ---- epilogue: digest of the final state, counters --------------------------------------------
