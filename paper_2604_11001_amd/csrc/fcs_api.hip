@@ -29,6 +29,7 @@ struct fcs_engine {
   fcs_outputs out{};
   int32_t lcap = 0, hcap = 0, hscap = 0;
   int64_t spill_stride = 0;
+  uint32_t launch_seq = 0;
   size_t blob_bytes_padded = 0;
   // last run
   bool ran = false;
@@ -218,6 +219,9 @@ int fcs_bind(fcs_handle h, void* ws, size_t bytes, int64_t n_replicas, const fcs
   hipError_t e = hipMemcpyAsync(ws, h->blob.data(), h->blob.size() * sizeof(uint32_t),
                                 hipMemcpyHostToDevice, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return FCS_EDEVICE;
+  // the last 256 bytes hold the pacing words of the kernel; they start at zero
+  if (hipMemsetAsync(static_cast<char*>(ws) + need - 256, 0, 256, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return FCS_EDEVICE;
   // the blob is pageable host memory owned by the handle: wait so it may change afterwards
   if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return FCS_EDEVICE;
   h->workspace = ws;
@@ -255,6 +259,12 @@ int fcs_run_from(fcs_handle h, int64_t replica_base, int64_t n_replicas, int64_t
   kp.n_trace = h->trace_every > 0 ? static_cast<int32_t>(n_steps / h->trace_every) : 0;
   kp.hist_bins = h->hist_bins; kp.hist_shift = h->hist_shift; kp.max_requests = h->max_requests;
   kp.n_paths = static_cast<int32_t>(n_replicas * h->n_cells);
+  {
+    size_t need = 0;
+    if (fcs_workspace_bytes(h, h->bound_replicas, &need) != FCS_OK) return FCS_ESTATE;
+    kp.pace = reinterpret_cast<unsigned long long*>(static_cast<char*>(h->workspace) + need - 256);
+    kp.launch_seq = ++h->launch_seq;
+  }
   kp.out = h->out;
   if (h->hist_bins == 0) kp.out.hist = nullptr;
   if (h->max_requests == 0) { kp.out.arrival_step = nullptr; kp.out.completion_step = nullptr; }

@@ -55,6 +55,9 @@ struct KParams {
   int64_t spill_stride;       // words per path
   int32_t trace_every, n_trace, hist_bins, hist_shift, max_requests;
   int32_t n_paths;
+  // pacing words ({sum of paces, paths} twice, used by alternate launches) or null
+  unsigned long long* pace;
+  uint32_t launch_seq;
   fcs_outputs out;
 };
 

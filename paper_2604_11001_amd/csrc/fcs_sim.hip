@@ -515,9 +515,49 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
     cal1 = (static_cast<uint64_t>(wave_or(hi1)) << 32) | wave_or(lo1);
   };
 
+  // A launch lasts as long as its slowest path and wavefronts share a SIMD, so a path that is
+  // behind the others gets issue priority over its neighbours.  Every eighth window a path
+  // publishes its pace (time per slot so far) into a sum over all paths of the launch and takes the
+  // priority that the mean it read the time before gives it (that read has had eight windows to
+  // arrive).  kp.pace holds {sum, count} twice: launches alternate between the two and clear the
+  // other one, so the words need no clearing from the host.
+  const unsigned long long t_begin = wall_clock64();
+  unsigned long long* const pace_w = kp.pace ? kp.pace + 2 * (kp.launch_seq & 1u) : nullptr;
+  if (kp.pace != nullptr && path == 0 && lane == 0) {
+    kp.pace[2 * ((kp.launch_seq & 1u) ^ 1u)] = 0ull;
+    kp.pace[2 * ((kp.launch_seq & 1u) ^ 1u) + 1] = 0ull;
+  }
+  unsigned long long pace_sum = 0, pace_cnt = 0;  // what this path last read
+  uint32_t pace_mine = 0;                          // what it last published
+  auto pacing = [&](int t0) __attribute__((always_inline)) {
+    if (pace_w == nullptr || ((t0 - 1) & 511) != 0 || t0 <= 1) return;
+    const unsigned long long dt = wall_clock64() - t_begin;
+    const uint32_t pace = static_cast<uint32_t>(min(dt * 64ull / static_cast<unsigned long long>(t0 - 1), 0xffffffull));
+    const unsigned long long sum = (static_cast<unsigned long long>(static_cast<uint32_t>(rfl(static_cast<int>(pace_sum >> 32)))) << 32) |
+                                   static_cast<uint32_t>(rfl(static_cast<int>(pace_sum)));
+    const uint32_t cnt = static_cast<uint32_t>(rfl(static_cast<int>(pace_cnt)));
+    if (lane == 0) {
+      // nothing comes back from the updates
+      __hip_atomic_fetch_add(pace_w, static_cast<unsigned long long>(pace) - static_cast<unsigned long long>(pace_mine),
+                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (pace_mine == 0) __hip_atomic_fetch_add(pace_w + 1, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      pace_sum = __hip_atomic_load(pace_w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      pace_cnt = __hip_atomic_load(pace_w + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    pace_mine = pace;
+    if (cnt != 0) {
+      const unsigned long long p = static_cast<unsigned long long>(pace) * cnt * 64ull;  // pace / mean in 64ths
+      if (p >= sum * 77ull) __builtin_amdgcn_s_setprio(3);        // 20 % slower than the mean
+      else if (p >= sum * 69ull) __builtin_amdgcn_s_setprio(2);   // 8 %
+      else if (p >= sum * 63ull) __builtin_amdgcn_s_setprio(1);   // about the mean
+      else __builtin_amdgcn_s_setprio(0);
+    }
+  };
+
   // First slot t0 of a 64-slot window: draws n_t and B_t of the window and rebuilds the calendar.
   int win_t0 = 0;
   auto window_start = [&](int t0) __attribute__((always_inline)) {
+    pacing(t0);
     int n, b;
     draw_slot(static_cast<uint32_t>(t0), n, b);
     win = n | (b << 16);
