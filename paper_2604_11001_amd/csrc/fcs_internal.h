@@ -33,7 +33,7 @@ constexpr int kSpillWordsPerSlot = 6;
 constexpr int S_NFIELDS = 4;
 
 constexpr int kWave = 64;
-constexpr int kGuideBits = 12;
+constexpr int kGuideBits = 16;
 constexpr int kLdsBlock = 256;       // slots per b128 pass over the LDS tier
 constexpr int kStackLds = 64;        // evicted-stack entries kept in LDS
 constexpr int kScratchWords = 64;

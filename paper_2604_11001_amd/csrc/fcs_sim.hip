@@ -241,6 +241,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   uint32_t rd_t = 1;   // reader cursor: slot ...
   int rd_k = 0;        // ... and arrivals of that slot already handed out
   int win = 0;         // lane i: n_t | B_t << 16 for the i-th slot of the current window
+  int win_t0 = 0;      // first slot of that window (0: none drawn yet)
   // calendars: bit i = some request may complete in the i-th slot of the current window; cal0 for
   // the requests in slots 0..255, cal1 for the others
   uint64_t cal0 = 0, cal1 = 0;
@@ -278,7 +279,8 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
     fb_count = 0;
     while (fb_count == 0 && rd_t <= static_cast<uint32_t>(T)) {
       int n, b;
-      draw_slot(rd_t, n, b);
+      if (rd_t == static_cast<uint32_t>(win_t0)) n = win & 0xffff;  // the window just drawn
+      else draw_slot(rd_t, n, b);
       if (rd_t + static_cast<uint32_t>(lane) > static_cast<uint32_t>(T)) n = 0;
       if (lane == 0) n -= rd_k;
       const int incl = wave_incl_sum(n);
@@ -555,7 +557,6 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
   };
 
   // First slot t0 of a 64-slot window: draws n_t and B_t of the window and rebuilds the calendar.
-  int win_t0 = 0;
   auto window_start = [&](int t0) __attribute__((always_inline)) {
     pacing(t0);
     int n, b;

@@ -184,3 +184,18 @@ def test_config4_full_size_sampled_paths():
     wl = configs.config4(oracle.stability_bound)
     eng, _ = _full_size(wl, [0, 511], "cfg4 full")
     assert eng.n_paths == 512 and eng.n_steps == 1000000
+
+
+def test_repeated_launches_are_identical():
+    # the kernel's pacing hints (wavefront priorities from a launch-wide mean pace) alternate between two
+    # copies of their words from launch to launch; results must not depend on them
+    wl = configs.toy(n_replicas=16, n_steps=2000)
+    eng = fcs.Engine(wl)
+    runs = []
+    for _ in range(3):
+        eng.run()
+        got, _ = eng.stats()
+        runs.append(got)
+    for k in runs[0]:
+        assert np.array_equal(runs[0][k], runs[1][k]) and np.array_equal(runs[0][k], runs[2][k]), k
+    compare(eng, wl, label="third launch")
