@@ -64,6 +64,9 @@ def main() -> int:
     ap.add_argument("--lds-slots", type=int, default=0)
     ap.add_argument("--max-active", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cells", type=str, default="", help="profiling aid: comma-separated subset of the cells")
+    ap.add_argument("--copy-mib", type=int, default=0,
+                    help="profiling aid: first run a plain device copy of this many MiB (scale for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this engine runs on one GPU; sample paths are independent, so several GPUs would "
@@ -81,6 +84,15 @@ def main() -> int:
     wl = configs.make(args.config, fcs.stability_bound)
     if args.replicas or args.slots:
         wl = wl.scaled(n_replicas=args.replicas, n_steps=args.slots)
+    if args.cells:
+        import dataclasses
+        wl = dataclasses.replace(wl, cells=tuple(wl.cells[int(i)] for i in args.cells.split(",")))
+    if args.copy_mib > 0:
+        src = torch.ones(args.copy_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     # statistics only: per-request records and histograms are parity-test outputs
     wl = wl.scaled(max_requests=0)
     eng = fcs.Engine(wl, max_active=args.max_active, lds_slots=args.lds_slots)
