@@ -754,14 +754,51 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
         // (all o tokens still to come) take token 1 for free
         int left = budget;
         advanced = 0;
-        for (int base = 0; base < n_slots; base += kWave) {
+        // LDS tier: four {END, FOOT} pairs per lane and pass, lanes in activation order
+        const int lim = min(n_slots, LC);
+        for (int b0 = 0; b0 < lim; b0 += kLdsBlock) {
+          const int p0 = b0 + (lane << 2);
+          v4i a = ld4(&smem[2 * p0]), b = ld4(&smem[2 * p0 + 4]);
+          int o0 = 0, o1 = 0, o2 = 0, o3 = 0;
+          if (new_dec > 0) {  // output lengths tell the requests that finished their prompt in this slot
+            o0 = smem[O_REC + 4 * p0 + 1]; o1 = smem[O_REC + 4 * p0 + 5];
+            o2 = smem[O_REC + 4 * p0 + 9]; o3 = smem[O_REC + 4 * p0 + 13];
+          }
+          const bool f0 = new_dec > 0 && a.x - t + 1 == o0, f1 = new_dec > 0 && a.z - t + 1 == o1;
+          const bool f2 = new_dec > 0 && b.x - t + 1 == o2, f3 = new_dec > 0 && b.z - t + 1 == o3;
+          const int d0 = a.x >= t && !f0, d1 = a.z >= t && !f1, d2 = b.x >= t && !f2, d3 = b.z >= t && !f3;
+          const int cnt = d0 + d1 + d2 + d3;
+          const int incl = wave_incl_sum(cnt);
+          const int total = rdl(incl, kWave - 1);
+          const int r0 = incl - cnt, r1 = r0 + d0, r2 = r1 + d1, r3 = r2 + d2;  // ranks among the old ones
+          const bool g0 = d0 && r0 < left, g1 = d1 && r1 < left, g2 = d2 && r2 < left, g3 = d3 && r3 < left;
+          const bool c0 = (g0 || (f0 && a.x >= t)) && a.x == t, c1 = (g1 || (f1 && a.z >= t)) && a.z == t;
+          const bool c2 = (g2 || (f2 && b.x >= t)) && b.x == t, c3 = (g3 || (f3 && b.z >= t)) && b.z == t;
+          const int ndone = c0 + c1 + c2 + c3;
+          const int relv = (c0 ? a.y : 0) + (c1 ? a.w : 0) + (c2 ? b.y : 0) + (c3 ? b.w : 0);
+          uint64_t m = __ballot(ndone != 0);
+          while (m != 0) {
+            const int i = __builtin_ctzll(m);
+            m &= m - 1;
+            n_done += rdl(ndone, i);
+            rel_sum += rdl(relv, i);
+          }
+          const int took = min(total, left);
+          if (took < total) {  // the requests past the budget finish one slot later
+            a.x += (d0 && !g0) ? 1 : 0; a.z += (d1 && !g1) ? 1 : 0;
+            b.x += (d2 && !g2) ? 1 : 0; b.z += (d3 && !g3) ? 1 : 0;
+            st4(&smem[2 * p0], a);
+            st4(&smem[2 * p0 + 4], b);
+          }
+          left -= took;
+          advanced += took;
+          wave_sync();
+        }
+        for (int base = LC; base < n_slots; base += kWave) {  // spill tier, 64 slots per pass
           const int pos = base + lane;
           const bool in = pos < n_slots;
           int v = -1, ov = 0;
-          if (in) {
-            if (base < LC) { v = smem[2 * pos]; ov = smem[O_REC + 4 * pos + 1]; }
-            else { v = hREM[pos - LC]; ov = hREC[4 * static_cast<size_t>(pos - LC) + 1]; }
-          }
+          if (in) { v = hREM[pos - LC]; ov = hREC[4 * static_cast<size_t>(pos - LC) + 1]; }
           const bool dec = v >= t;
           const bool fresh = dec && new_dec > 0 && v - t + 1 == ov;
           const bool old = dec && !fresh;
@@ -773,9 +810,7 @@ __global__ __launch_bounds__(kWave) void fcs_sim_kernel(const KParams kp) {
           const bool d = go && v == t;
           const uint64_t dm = __ballot(d);
           if (dm != 0) complete(d, dm, pos);
-          if (old && !go) {
-            if (base < LC) smem[2 * pos] = v + 1; else hREM[pos - LC] = v + 1;
-          }
+          if (old && !go) hREM[pos - LC] = v + 1;
           wave_sync();
         }
         // a stalled request moved to the next slot: keep the calendars supersets
