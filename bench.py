@@ -53,6 +53,31 @@ def cpu_baseline(config_index: int, target_seconds: float = 15.0):
                       f"({total} request-steps in {dt:.2f} s)"}
 
 
+def measured_traffic(config_index):
+    """HBM bytes per launch from the committed rocprofv3 counter run, or None once the kernel sources
+    differ from the ones the counters were taken on (or for another configuration)."""
+    import glob
+    import hashlib
+    if config_index != 1:
+        return None
+    path = os.path.join(ROOT, "profiles", "fcs_sim_kernel_cfg1_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for ln in open(path):
+        if ln.startswith("#") or ":" not in ln:
+            continue
+        k, v = ln.split(":", 1)
+        vals[k.strip()] = v.strip()
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2604_11001_amd", "csrc", "*"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    if h.hexdigest() != vals.get("source_sha256"):
+        return None
+    return int(vals["fetch_bytes_per_launch"]) + int(vals["write_bytes_per_launch"])
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -128,7 +153,8 @@ def main() -> int:
                    "lds_bytes_per_path": geo["lds_bytes"], "spill_slots": geo["spill_slots"],
                    "evictions": int(summary["evictions"]), "completed": int(summary["completed"])},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None if (args.cells or args.replicas or args.slots) else measured_traffic(args.config),
                      "kernel": "fcs_sim_kernel", "kernel_ms": sum(kernel_ms) / len(kernel_ms),
                      "bytes_per_request_step": BYTES_PER_REQUEST_STEP},
     }
