@@ -44,6 +44,8 @@ class _Config(C.Structure):
         ("forced_t", C.POINTER(C.c_int32)), ("forced_l", C.POINTER(C.c_int32)),
         ("forced_o", C.POINTER(C.c_int32)),
         ("n_forced_B", C.c_int64), ("forced_B", C.POINTER(C.c_int32)),
+        ("class_arrivals", C.POINTER(_Law)), ("class_budget", C.POINTER(C.c_int32)),
+        ("forced_cls", C.POINTER(C.c_int32)),
     ]
 
 
@@ -116,7 +118,8 @@ def run_cell(wl, cell_index, replica_ids=None, n_steps=None, seed=None, n_thread
     ``arrival_step``, ``completion_step`` and (oracle-only) ``first_activation``,
     ``last_activation``, ``req_l``, ``req_o``, ``step_*``.
     ``forced`` = (t, l, o) arrays replaces the random arrival stream and
-    ``forced_B`` the random activation budgets (hand-computed trajectories).
+    ``forced_B`` the random activation budgets (hand-computed trajectories); for a
+    CLASSES cell ``forced`` = (t, class) arrays.
     """
     cell = wl.cells[cell_index]
     T = int(wl.n_steps if n_steps is None else n_steps)
@@ -148,7 +151,20 @@ def run_cell(wl, cell_index, replica_ids=None, n_steps=None, seed=None, n_thread
     cfg.hist_shift = int(wl.hist_shift)
     cfg.max_requests = max_req
     cfg.n_forced = -1
-    if forced is not None:
+    if cell.policy == 2:
+        ca = (_Law * nc)(*[_law(wl.arrival_laws[a], keep) for a in cell.class_arrival])
+        cb = np.ascontiguousarray(cell.class_budget, dtype=np.int32)
+        keep += [ca, cb]
+        cfg.class_arrivals = ca
+        cfg.class_budget = _p(cb, C.c_int32)
+        if forced is not None:
+            ft, fc = (np.ascontiguousarray(a, dtype=np.int32) for a in forced)
+            if np.any(np.diff(ft) < 0):
+                raise ValueError("forced arrivals must be sorted by slot")
+            keep += [ft, fc]
+            cfg.n_forced = int(ft.size)
+            cfg.forced_t, cfg.forced_cls = _p(ft, C.c_int32), _p(fc, C.c_int32)
+    elif forced is not None:
         ft, fl, fo = (np.ascontiguousarray(a, dtype=np.int32) for a in forced)
         if np.any(np.diff(ft) < 0):
             raise ValueError("forced arrivals must be sorted by slot")

@@ -1,5 +1,6 @@
 // Plain CPU oracle for the slot-level model of one LLM-serving worker and the
-// flow-control admission rule (Section 2.1; Algorithm 2; Section 3.3).
+// flow-control admission rules (Section 2.1; Algorithm 2, Section 3.3; Algorithm 1,
+// Section 3.2).
 //
 // THIS FILE IS TEST INFRASTRUCTURE.  It is the slow, obviously-correct statement
 // of what a sample path is; only the tests, the smoke check and the benchmark's
@@ -15,6 +16,12 @@
 //                     GREEDY: the b -> infinity limit described after Theorem 2, with the
 //                             "initial memory l+1" fit test of Section 4.1: move the head
 //                             while usage-after-this-slot + l + 1 <= M.
+//                     CLASSES: Algorithm 1 (known lengths): every class k has its own arrival
+//                             stream n_{t,k}, its own FIFO and an integer budget b_k; in
+//                             class order, min(b_k, |Q_k|) head requests of class k move
+//                             to P.  There is no overflow branch in Algorithm 1 (Theorem 1
+//                             keeps the usage below M when sum_k b_k w_k < M): step 3 only
+//                             counts the slots in which the provisioned usage exceeds M.
 //   3. overflow       Algorithm 2 "if Overflow": the usage this slot is about to reach is
 //                     sum(l+j) + |P| (each active request may gain one token); while it
 //                     exceeds M evict the most recently activated request (LIFO rule of
@@ -35,8 +42,10 @@
 // Random draws: Philox4x32-10 (Salmon et al., SC'11), key = (seed lo, seed hi),
 // counter = (k, t, replica, purpose); purpose 0, k = 0: word0 -> n_t, word1 -> B_t;
 // purpose 1, k = index of the arrival within its slot: word0 -> class, word1 -> l,
-// word2 -> o.  Each word is inverted against a uint32 threshold table:
-// value = lo + #{i : u >= thr[i]}.
+// word2 -> o; purpose 2 (CLASSES), k = class: word0 -> n_{t,k}, and the requests of class k
+// all have l = lo of its prompt law and o = lo of its decode law (both must be point laws);
+// their ids are (index within the class) * n_classes + k.  Each word is inverted against a
+// uint32 threshold table: value = lo + #{i : u >= thr[i]}.
 //
 // parity unpinned: the budget order of step 4, the provisioned-usage reading of
 // "Overflow" in step 3 and the front-of-queue re-entry are this build's readings of
@@ -58,7 +67,7 @@ struct fo_law {
 };
 
 struct fo_config {
-  int32_t policy;  // 0 FLOW, 1 GREEDY
+  int32_t policy;  // 0 FLOW, 1 GREEDY, 2 CLASSES
   int32_t n_classes;
   int64_t capacity;
   int64_t token_budget;
@@ -81,6 +90,10 @@ struct fo_config {
   const int32_t* forced_o;
   int64_t n_forced_B;  // 0: draw B_t; else B_t = forced_B[min(t, n) - 1]
   const int32_t* forced_B;
+  // CLASSES only
+  const fo_law* class_arrivals;  // n_classes laws of n_{t,k}
+  const int32_t* class_budget;   // n_classes budgets b_k
+  const int32_t* forced_cls;     // class of each forced arrival (with n_forced >= 0)
 };
 
 enum {
@@ -173,6 +186,7 @@ int64_t invert_sorted(const fo_law& law, uint32_t u) {
 
 struct Request {
   int64_t id, l, o, t_arr;
+  int64_t cls = 0;
   int64_t p = 0;  // prompt tokens prefilled
   int64_t j = 0;  // output tokens generated
   bool was_active = false;
@@ -192,6 +206,9 @@ void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, i
   const uint32_t key[2] = {static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32)};
   const int64_t M = cfg.capacity;
   std::deque<Request> Q;
+  const bool by_class = cfg.policy == 2;
+  std::vector<std::deque<Request>> Qk(by_class ? cfg.n_classes : 0);  // CLASSES: one FIFO per class
+  std::vector<int64_t> next_in_class(by_class ? cfg.n_classes : 0, 0);
   std::vector<Request> P;
   uint64_t* C = out.counters + slot * FO_N_COUNTERS;
   std::memset(C, 0, sizeof(uint64_t) * FO_N_COUNTERS);
@@ -210,7 +227,33 @@ void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, i
       philox4x32_10(ctr, key, blk);
     }
     int64_t n_t = 0;
-    if (cfg.n_forced >= 0) {
+    if (by_class) {
+      auto arrive = [&](int64_t k) {
+        Request r;
+        r.cls = k;
+        r.id = next_in_class[k]++ * cfg.n_classes + k;
+        r.l = cfg.prompt[k].lo;
+        r.o = cfg.decode[k].lo;
+        r.t_arr = t;
+        Qk[k].push_back(r);
+        rec(out.arrival_step, r.id, t);
+        rec(out.req_l, r.id, r.l);
+        rec(out.req_o, r.id, r.o);
+        ++n_t;
+      };
+      if (cfg.n_forced >= 0) {
+        while (forced_pos < cfg.n_forced && cfg.forced_t[forced_pos] == t) arrive(cfg.forced_cls[forced_pos++]);
+      } else {
+        for (int64_t k = 0; k < cfg.n_classes; ++k) {
+          const uint32_t ctr[4] = {static_cast<uint32_t>(k), static_cast<uint32_t>(t),
+                                   static_cast<uint32_t>(replica), 2u};
+          uint32_t w[4];
+          philox4x32_10(ctr, key, w);
+          const int64_t n_tk = invert(cfg.class_arrivals[k], w[0]);
+          for (int64_t i = 0; i < n_tk; ++i) arrive(k);
+        }
+      }
+    } else if (cfg.n_forced >= 0) {
       while (forced_pos < cfg.n_forced && cfg.forced_t[forced_pos] == t) {
         Request r;
         r.id = next_id++;
@@ -238,7 +281,7 @@ void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, i
         Q.push_back(r);
       }
     }
-    for (int64_t k = 0; k < n_t; ++k) {
+    for (int64_t k = 0; k < n_t && !by_class; ++k) {
       const Request& r = Q[Q.size() - n_t + k];
       rec(out.arrival_step, r.id, t);
       rec(out.req_l, r.id, r.l);
@@ -259,7 +302,17 @@ void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, i
       P.push_back(r);
       C[FO_ACTIVATIONS] += 1;
     };
-    if (cfg.policy == 0) {
+    if (by_class) {
+      for (int64_t k = 0; k < cfg.n_classes; ++k) {
+        int64_t activated = 0;
+        while (activated < cfg.class_budget[k] && !Qk[k].empty()) {
+          Q.push_front(Qk[k].front());  // through the common helper: it takes the head of Q
+          Qk[k].pop_front();
+          activate_head();
+          ++activated;
+        }
+      }
+    } else if (cfg.policy == 0) {
       if (cfg.n_forced_B > 0)
         B_t = cfg.forced_B[std::min<int64_t>(t, cfg.n_forced_B) - 1];
       else
@@ -279,7 +332,8 @@ void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, i
 
     // ---- 3. overflow: evict newest until the provisioned usage fits ---------
     bool overflowed = false;
-    while (usage(P) + static_cast<int64_t>(P.size()) > M) {
+    if (by_class && usage(P) + static_cast<int64_t>(P.size()) > M) overflowed = true;  // counted, nobody leaves
+    while (!by_class && usage(P) + static_cast<int64_t>(P.size()) > M) {
       Request r = P.back();
       P.pop_back();
       r.p = 0;
@@ -318,7 +372,8 @@ void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, i
     // ---- 5. measure ----------------------------------------------------------
     const int64_t U_t = usage(P);
     const int64_t P_t = static_cast<int64_t>(P.size());
-    const int64_t Q_t = static_cast<int64_t>(Q.size());
+    int64_t Q_t = static_cast<int64_t>(Q.size());
+    for (const auto& q : Qk) Q_t += static_cast<int64_t>(q.size());
     C[FO_SUM_U] += U_t;
     C[FO_SUM_P] += P_t;
     C[FO_SUM_Q] += Q_t;
@@ -360,6 +415,7 @@ void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, i
 
   C[FO_FINAL_P] = P.size();
   C[FO_FINAL_Q] = Q.size();
+  for (const auto& q : Qk) C[FO_FINAL_Q] += q.size();
   C[FO_FINAL_U] = usage(P);
   // digest of the final state: FNV-1a over 64-bit words
   uint64_t h = 14695981039346656037ull;
@@ -369,12 +425,16 @@ void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, i
     h = fnv_step(h, r.j);
     h = fnv_step(h, r.p);
   }
-  uint64_t returned = 0;
-  for (const Request& r : Q) returned += r.was_active ? 1 : 0;
-  h = fnv_step(h, returned);
-  for (const Request& r : Q)
-    if (r.was_active) h = fnv_step(h, r.id);
-  h = fnv_step(h, Q.size() - returned);
+  if (by_class) {  // the waiting requests of a class are interchangeable: their number says it all
+    for (const auto& q : Qk) h = fnv_step(h, q.size());
+  } else {
+    uint64_t returned = 0;
+    for (const Request& r : Q) returned += r.was_active ? 1 : 0;
+    h = fnv_step(h, returned);
+    for (const Request& r : Q)
+      if (r.was_active) h = fnv_step(h, r.id);
+    h = fnv_step(h, Q.size() - returned);
+  }
   C[FO_DIGEST] = h;
 }
 
@@ -411,7 +471,13 @@ int fo_invert(const fo_law* law, const uint32_t* u, int64_t n, int64_t* out) {
 int fo_run(const fo_config* cfg, int64_t n_ids, const int64_t* replica_ids, int64_t n_steps,
            uint64_t seed, int32_t n_threads, const fo_outputs* out) {
   if (!cfg || !out || !out->counters || n_ids < 0 || n_steps < 0) return -1;
-  if (cfg->policy != 0 && cfg->policy != 1) return -1;
+  if (cfg->policy < 0 || cfg->policy > 2) return -1;
+  if (cfg->policy == 2) {
+    if (!cfg->class_budget || (cfg->n_forced < 0 && !cfg->class_arrivals)) return -1;
+    if (cfg->n_forced >= 0 && !cfg->forced_cls) return -1;
+    for (int32_t k = 0; k < cfg->n_classes; ++k)
+      if (cfg->prompt[k].n_thr != 0 || cfg->decode[k].n_thr != 0 || cfg->class_budget[k] < 0) return -1;
+  }
   if (cfg->capacity < 1 || cfg->token_budget < 1 || cfg->prefill_chunk < 1) return -1;
   if (n_threads < 1) n_threads = 1;
   if (out->hist && cfg->hist_bins > 0)

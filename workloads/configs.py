@@ -24,6 +24,7 @@ from .laws import Law, Mixture, RequestClass
 
 FLOW = 0     # Algorithm 2: rate-limited activation, LIFO eviction on overflow
 GREEDY = 1   # b -> infinity limit with a memory fit test: admit while it fits, evict newest
+CLASSES = 2  # Algorithm 1: known lengths, one FIFO, arrival stream and integer budget b_k per class
 
 
 @dataclasses.dataclass(frozen=True)
@@ -33,6 +34,8 @@ class Cell:
     b_floor: int          # B_t = b_floor + [u < b_frac_thr]   (ignored by GREEDY)
     b_frac_thr: int
     label: str = ""
+    class_arrival: tuple = ()   # CLASSES: per class, index into Workload.arrival_laws
+    class_budget: tuple = ()    # CLASSES: per class, integer budget b_k
 
 
 @dataclasses.dataclass(frozen=True)
@@ -85,6 +88,14 @@ def flow_cell(arrival: int, b: float, label: str = "") -> Cell:
 
 def greedy_cell(arrival: int, label: str = "greedy") -> Cell:
     return Cell(GREEDY, arrival, 0, 0, label)
+
+
+def classes_cell(class_arrival, class_budget, label: str = "") -> Cell:
+    class_arrival = tuple(int(a) for a in class_arrival)
+    class_budget = tuple(int(b) for b in class_budget)
+    if len(class_arrival) != len(class_budget):
+        raise ValueError("one arrival law and one budget per class")
+    return Cell(CLASSES, class_arrival[0], 0, 0, label or f"classes(b={class_budget})", class_arrival, class_budget)
 
 
 Bound = Callable[[Mixture, int], float]
@@ -178,6 +189,23 @@ def three_class(lam_per_class: float, capacity: int = 16492, b: float = 12.0,
         arrival_laws=(laws.poisson_counts(3.0 * lam_per_class),),
         cells=(flow_cell(0, b), greedy_cell(0)),
         n_replicas=n_replicas, n_steps=n_steps, seed=seed, max_requests=1 << 16)
+
+
+def known_classes(lam_per_class=(5.0, 5.0, 5.0), budgets=(4, 4, 4), lengths=((10, 20), (10, 40), (10, 60)),
+                  capacity: int = 16492, token_budget: int = 1 << 30, prefill_chunk: int = 1 << 30,
+                  n_replicas: int = 1024, n_steps: int = 10_000, seed: int = 8, **kw) -> Workload:
+    """The paper's synthetic study with known lengths (Section 4.1 under Algorithm 1): classes
+    (l, o) = (10, 20), (10, 40), (10, 60), Poisson arrivals per class, M = 16492, b = (4, 4, 4).
+    The printed rate of 5 per class overloads it (b_k < lambda_k); rates below 4 are stable."""
+    cls = tuple(RequestClass(1.0, laws.point(l), laws.point(o)) for l, o in lengths)
+    rates = tuple(float(x) for x in lam_per_class)
+    distinct = sorted(set(rates))
+    arr = tuple(laws.poisson_counts(r) for r in distinct)
+    cell = classes_cell([distinct.index(r) for r in rates], budgets)
+    return Workload(
+        name="known-classes", capacity=capacity, token_budget=token_budget, prefill_chunk=prefill_chunk,
+        mixture=Mixture(cls), arrival_laws=arr, cells=(cell,), n_replicas=n_replicas, n_steps=n_steps,
+        seed=seed, **kw)
 
 
 def toy(capacity: int = 600, token_budget: int = 96, prefill_chunk: int = 32, lam: float = 0.6,
