@@ -4,8 +4,9 @@
  * The engine evaluates, as many independent sample paths, the slotted model of
  * one LLM-serving worker with a KV-cache budget M (Section 2.1 of the paper)
  * under the flow-control admission rule with unknown output length
- * (Algorithm 2, Section 3.3) and under its greedy limit (remark after
- * Theorem 2; fit test "initial memory l+1" of Section 4.1), extended by a
+ * (Algorithm 2, Section 3.3), under its greedy limit (remark after
+ * Theorem 2; fit test "initial memory l+1" of Section 4.1) and under the
+ * rule for known output lengths (Algorithm 1, Section 3.2), extended by a
  * per-slot token budget and chunked prefill (Section 1 describes both as
  * current practice; the paper's pure model is recovered with chunk >= l_max
  * and an unlimited budget).
@@ -15,8 +16,14 @@
  *   2. admission.  FLOW: the first min(B_t, |Q|) requests of Q join the active
  *      set P, B_t = b_floor + [u < b_frac_thr].  GREEDY: the head of Q joins
  *      while (sum_P (l+j)) + |P| + l_head + 1 <= M.
+ *      CLASSES (Algorithm 1): every class k of the length mixture has its own
+ *      arrival stream n_{t,k}, its own FIFO queue and an integer budget b_k; in
+ *      class order the first min(b_k, |Q_k|) requests of class k join P.
  *   3. overflow.  While (sum_P (l+j)) + |P| > M the most recently activated
  *      request is evicted: it loses its progress and returns to the FRONT of Q.
+ *      CLASSES: Algorithm 1 has no such step (Theorem 1 keeps the usage below M
+ *      when sum_k b_k w_k < M); the slots in which the condition holds are only
+ *      counted in FCS_C_OVERFLOW_STEPS and the usage may exceed M.
  *   4. processing with token budget tau and chunk c.  Prefilling requests, in
  *      activation order, advance min(c, l-p, budget left); the slot in which
  *      the prompt ends also yields output token 1 at no extra budget.  Then the
@@ -30,7 +37,10 @@
  * counter (k, t, replica, purpose).  purpose 0, k 0: word 0 -> n_t, word 1 ->
  * B_t.  purpose 1, k = index of the arrival within slot t: word 0 -> class,
  * word 1 -> l, word 2 -> o.  A word u is inverted against a law's threshold
- * table: value = lo + #{ i : u >= thr[i] }.  All cells of one engine see the
+ * table: value = lo + #{ i : u >= thr[i] }.  CLASSES cells use purpose 2
+ * instead, k = class: word 0 -> n_{t,k}; all requests of class k have l = lo of
+ * its prompt law and o = lo of its decode law, which must be point laws, and
+ * their ids are (index within the class) * n_classes + k.  All cells of one engine see the
  * same words (the policy and the cell are not part of the counter), so cells
  * are compared on identical arrival streams.
  *
@@ -65,7 +75,7 @@ enum {
   FCS_EDEVICE = -5    /* HIP error or no device                                   */
 };
 
-enum { FCS_POLICY_FLOW = 0, FCS_POLICY_GREEDY = 1 };
+enum { FCS_POLICY_FLOW = 0, FCS_POLICY_GREEDY = 1, FCS_POLICY_CLASSES = 2 };
 
 /* Integer law on {lo, ..., lo + n_thr}; thr non-decreasing (host pointer). */
 typedef struct fcs_law {
@@ -80,6 +90,9 @@ typedef struct fcs_cell {
   int32_t arrival;     /* index into fcs_params.arrival                            */
   int32_t b_floor;     /* FLOW: B_t = b_floor + [u < b_frac_thr]  (Theorem 2: any  */
   uint32_t b_frac_thr; /*   bounded i.i.d. integer budget with mean b)             */
+  const int32_t* class_arrival; /* CLASSES: n_classes indices into fcs_params.arrival, */
+                                /*   the law of n_{t,k} of each class (host pointer)   */
+  const int32_t* class_budget;  /* CLASSES: n_classes budgets b_k, 0 .. 64, sum <= 64  */
 } fcs_cell;
 
 typedef struct fcs_params {
@@ -98,7 +111,9 @@ typedef struct fcs_params {
   int32_t hist_bins;      /* > 0: latency histogram, bucket = min(lat >> shift, bins-1) */
   int32_t hist_shift;
   int32_t max_requests;   /* > 0: per-path length of arrival_step/completion_step  */
-  int32_t max_active;     /* per-path capacity of the active set; 0 = default      */
+  int32_t max_active;     /* per-path capacity of the active set; 0 = default:
+                           * M / (min l + 1) + 1, and with CLASSES cells at least
+                           * sum_k b_k (ceil(l_k / min(c, tau)) + o_k + 1); at most 8192 */
   int32_t lds_slots;      /* active-set slots kept in LDS per path; 0 = automatic  */
 } fcs_params;
 
@@ -108,7 +123,8 @@ enum {
   FCS_C_ACTIVATIONS,     /* activations, re-activations after eviction included     */
   FCS_C_COMPLETED,
   FCS_C_EVICTIONS,
-  FCS_C_OVERFLOW_STEPS,  /* slots with at least one eviction                        */
+  FCS_C_OVERFLOW_STEPS,  /* slots in which U_t + |P_t| passed M after admission:
+                          * with at least one eviction, or (CLASSES) only counted  */
   FCS_C_SUM_U,           /* sum_t U_t                                               */
   FCS_C_SUM_P,           /* sum_t |P_t| : the request-steps of the path             */
   FCS_C_SUM_Q,           /* sum_t |Q_t|                                             */
@@ -134,7 +150,8 @@ enum {
  * Words: |P|; for each active request in activation order: id, j, p; the number
  * of waiting requests that were active before; their ids in queue order; the
  * number of waiting requests never activated.  ids number a path's arrivals
- * 0,1,2,... in order of (slot, index within slot). */
+ * 0,1,2,... in order of (slot, index within slot).  CLASSES: after the active
+ * requests come n_classes words, the number of waiting requests of each class. */
 
 /* Device output arrays (caller-owned).  counters is required; the others may be
  * NULL, and must be non-NULL only if the matching parameter is > 0 and wanted. */

@@ -32,7 +32,8 @@ class fcs_law(C.Structure):
 
 class fcs_cell(C.Structure):
     _fields_ = [("policy", C.c_int32), ("arrival", C.c_int32), ("b_floor", C.c_int32),
-                ("b_frac_thr", C.c_uint32)]
+                ("b_frac_thr", C.c_uint32),
+                ("class_arrival", C.POINTER(C.c_int32)), ("class_budget", C.POINTER(C.c_int32))]
 
 
 class fcs_params(C.Structure):
@@ -131,8 +132,16 @@ def make_params(wl, max_active: int = 0, lds_slots: int = 0):
     arrival = (fcs_law * na)(*[_law(a, keep) for a in wl.arrival_laws])
     cthr = np.ascontiguousarray(mix.class_thr, dtype=np.uint32)
     ncell = len(wl.cells)
-    cells = (fcs_cell * ncell)(*[fcs_cell(int(c.policy), int(c.arrival), int(c.b_floor), int(c.b_frac_thr))
-                                  for c in wl.cells])
+    cells = (fcs_cell * ncell)()
+    for i, c in enumerate(wl.cells):
+        cells[i].policy, cells[i].arrival = int(c.policy), int(c.arrival)
+        cells[i].b_floor, cells[i].b_frac_thr = int(c.b_floor), int(c.b_frac_thr)
+        if getattr(c, "class_arrival", ()):  # per-class arrival laws and budgets (Algorithm 1)
+            ca = np.ascontiguousarray(c.class_arrival, dtype=np.int32)
+            cb = np.ascontiguousarray(c.class_budget, dtype=np.int32)
+            keep += [ca, cb]
+            cells[i].class_arrival = ca.ctypes.data_as(C.POINTER(C.c_int32))
+            cells[i].class_budget = cb.ctypes.data_as(C.POINTER(C.c_int32))
     keep += [prompt, decode, arrival, cthr, cells]
     p = fcs_params()
     p.capacity, p.token_budget, p.prefill_chunk = int(wl.capacity), int(wl.token_budget), int(wl.prefill_chunk)

@@ -30,6 +30,8 @@ struct fcs_engine {
   int32_t lcap = 0, hcap = 0, hscap = 0;
   int64_t spill_stride = 0;
   uint32_t launch_seq = 0;
+  bool has_classes = false;
+  int64_t classes_active = 0;  // CLASSES: most requests active at once when no prefill ever waits
   size_t blob_bytes_padded = 0;
   // last run
   bool ran = false;
@@ -74,9 +76,20 @@ bool params_ok(const fcs_params* p) {
   if (p->n_cells < 1 || !p->cells) return false;
   for (int32_t i = 0; i < p->n_cells; ++i) {
     const fcs_cell& c = p->cells[i];
-    if (c.policy != FCS_POLICY_FLOW && c.policy != FCS_POLICY_GREEDY) return false;
+    if (c.policy != FCS_POLICY_FLOW && c.policy != FCS_POLICY_GREEDY && c.policy != FCS_POLICY_CLASSES) return false;
     if (c.arrival < 0 || c.arrival >= p->n_arrival_laws) return false;
     if (c.b_floor < 0 || c.b_floor > 30000) return false;
+    if (c.policy == FCS_POLICY_CLASSES) {  // Algorithm 1: known lengths, integer budgets
+      if (!c.class_arrival || !c.class_budget) return false;
+      int64_t total = 0;
+      for (int32_t k = 0; k < p->n_classes; ++k) {
+        if (p->prompt[k].n_thr != 0 || p->decode[k].n_thr != 0) return false;
+        if (c.class_arrival[k] < 0 || c.class_arrival[k] >= p->n_arrival_laws) return false;
+        if (c.class_budget[k] < 0 || c.class_budget[k] > kWave) return false;
+        total += c.class_budget[k];
+      }
+      if (total > kWave) return false;
+    }
   }
   if (p->trace_every < 0 || p->hist_bins < 0 || p->hist_bins > (1 << 24)) return false;
   if (p->hist_shift < 0 || p->hist_shift > 30 || p->max_requests < 0) return false;
@@ -152,6 +165,24 @@ int fcs_create(const fcs_params* p, fcs_handle* out) {
   for (int32_t a = 0; a < p->n_arrival_laws; ++a) append_law(body, laws, p->arrival[a], false);
   for (int32_t c = 0; c < p->n_classes; ++c) append_law(body, laws, p->prompt[c], true);
   for (int32_t c = 0; c < p->n_classes; ++c) append_law(body, laws, p->decode[c], true);
+  std::vector<uint32_t> class_table_off(p->n_cells, 0u);
+  for (int32_t i = 0; i < p->n_cells; ++i) {
+    if (p->cells[i].policy != FCS_POLICY_CLASSES) continue;
+    h->has_classes = true;
+    // Algorithm 1 admits b_k requests of class k per slot and never evicts, so M does not bound the
+    // active set; a request that is never held up stays ceil(l_k / chunk) + o_k slots
+    int64_t active = 0;
+    const int64_t chunk = std::max<int64_t>(1, std::min<int64_t>(p->prefill_chunk, p->token_budget));
+    for (int32_t k = 0; k < p->n_classes; ++k)
+      active += static_cast<int64_t>(p->cells[i].class_budget[k]) *
+                ((p->prompt[k].lo + chunk - 1) / chunk + p->decode[k].lo + 1);
+    h->classes_active = std::max(h->classes_active, active);
+    class_table_off[i] = head_words + static_cast<uint32_t>(body.size());
+    for (int32_t k = 0; k < p->n_classes; ++k) {
+      body.push_back(static_cast<uint32_t>(p->cells[i].class_arrival[k]));
+      body.push_back(static_cast<uint32_t>(p->cells[i].class_budget[k]));
+    }
+  }
   for (DLaw& d : laws) { d.off += head_words; if (d.goff) d.goff += head_words; }
   h->laws_off = 0;
   h->cells_off = static_cast<uint32_t>(4 * n_laws);
@@ -160,6 +191,7 @@ int fcs_create(const fcs_params* p, fcs_handle* out) {
   std::memcpy(h->blob.data(), laws.data(), sizeof(DLaw) * laws.size());
   for (int32_t i = 0; i < p->n_cells; ++i) {
     DCell d{p->cells[i].policy, p->cells[i].arrival, p->cells[i].b_floor, p->cells[i].b_frac_thr};
+    if (d.policy == FCS_POLICY_CLASSES) d.b_frac_thr = class_table_off[i];
     h->cells.push_back(d);
     std::memcpy(h->blob.data() + h->cells_off + 4 * i, &d, sizeof(d));
   }
@@ -175,7 +207,7 @@ static int geometry_for(fcs_engine* h, int64_t n_replicas, int32_t* lcap, int32_
   const int64_t n_paths = n_replicas * h->n_cells;
   if (n_paths > (1ll << 30)) return FCS_EINVAL;
   int64_t max_active = h->max_active;
-  if (max_active == 0) max_active = std::min<int64_t>(h->M / (h->l_min + 1) + 1, 8192);
+  if (max_active == 0) max_active = std::min<int64_t>(std::max<int64_t>(h->M / (h->l_min + 1) + 1, h->classes_active), 8192);
   max_active = static_cast<int64_t>(round_up(static_cast<size_t>(max_active), kWave));
   int32_t lc = h->lds_slots_param;
   if (lc == 0) {
@@ -185,7 +217,8 @@ static int geometry_for(fcs_engine* h, int64_t n_replicas, int32_t* lcap, int32_
     // wavefronts per unit buy less than running each of them in that loop)
     int64_t per_cu = (n_paths + 255) / 256;
     per_cu = std::min<int64_t>(std::max<int64_t>(per_cu, 4), 8);
-    const int64_t words = (160 * 1024 / per_cu) / 4 - S_NFIELDS * kStackLds - kScratchWords;
+    const int64_t words = (160 * 1024 / per_cu) / 4 - S_NFIELDS * kStackLds - kScratchWords -
+                          (h->has_classes ? class_lds_words(h->n_classes) : 0);
     lc = static_cast<int32_t>(words / kLdsWordsPerSlot / kLdsBlock * kLdsBlock);
     lc = std::min(std::max(lc, kLdsBlock), 2048);
   }
@@ -253,6 +286,7 @@ int fcs_run_from(fcs_handle h, int64_t replica_base, int64_t n_replicas, int64_t
   kp.seed_lo = static_cast<uint32_t>(seed);
   kp.seed_hi = static_cast<uint32_t>(seed >> 32);
   kp.lcap = h->lcap; kp.hcap = h->hcap; kp.hscap = h->hscap;
+  kp.class_words = h->has_classes ? class_lds_words(h->n_classes) : 0;
   kp.spill = reinterpret_cast<int32_t*>(static_cast<char*>(h->workspace) + h->blob_bytes_padded);
   kp.spill_stride = h->spill_stride;
   kp.trace_every = h->trace_every;
@@ -400,7 +434,7 @@ int fcs_geometry(fcs_handle h, int32_t* lds_slots, int32_t* lds_bytes, int32_t* 
   if (!h) return FCS_EINVAL;
   if (!h->bound) return FCS_ESTATE;
   if (lds_slots) *lds_slots = h->lcap;
-  if (lds_bytes) *lds_bytes = lds_words(h->lcap) * 4;
+  if (lds_bytes) *lds_bytes = lds_words(h->lcap, h->has_classes ? class_lds_words(h->n_classes) : 0) * 4;
   if (spill_slots) *spill_slots = h->hcap;
   return FCS_OK;
 }

@@ -22,7 +22,7 @@ struct DCell {
   int32_t policy;
   int32_t arrival;
   int32_t b_floor;
-  uint32_t b_frac_thr;
+  uint32_t b_frac_thr;  // CLASSES: word offset in the blob of {arrival law, budget} x n_classes
 };
 
 // Words of one active-set slot: in LDS {END, footprint} pairs, PLEFT and the 4-word record; in the
@@ -51,6 +51,7 @@ struct KParams {
   int32_t n_steps;
   uint32_t seed_lo, seed_hi;
   int32_t lcap, hcap, hscap;  // LDS slots, spill slots, spill stack entries (per path)
+  int32_t class_words;        // LDS words of the per-class tables (0 without CLASSES cells)
   int32_t* spill;             // per path: kSpillWordsPerSlot*hcap + S_NFIELDS*hscap words
   int64_t spill_stride;       // words per path
   int32_t trace_every, n_trace, hist_bins, hist_shift, max_requests;
@@ -61,7 +62,12 @@ struct KParams {
   fcs_outputs out;
 };
 
-inline int lds_words(int lcap) { return kLdsWordsPerSlot * lcap + S_NFIELDS * kStackLds + kScratchWords; }
+// CLASSES cells keep two tables of 64 arrival counts per class in LDS (current window, and the
+// block the reader of each class queue stands in)
+inline int class_lds_words(int n_classes) { return 2 * kWave * n_classes; }
+inline int lds_words(int lcap, int class_words) {
+  return kLdsWordsPerSlot * lcap + S_NFIELDS * kStackLds + kScratchWords + class_words;
+}
 
 // Defined in fcs_sim.hip; launches one single-wavefront workgroup per path.
 int launch_sim(const KParams& kp, void* stream);

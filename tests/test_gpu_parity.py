@@ -186,6 +186,62 @@ def test_config4_full_size_sampled_paths():
     assert eng.n_paths == 512 and eng.n_steps == 1000000
 
 
+# ---- Algorithm 1 (Section 3.2): known lengths, one FIFO queue and one integer budget per class ----------
+
+def test_algorithm1_small_cases():
+    obs = dict(trace_every=25, hist_bins=512, max_requests=1 << 15)
+    cases = {
+        # the paper's three classes at the printed rates: budgets below the rates, queues grow
+        "overloaded": configs.known_classes(n_replicas=8, n_steps=1500, **obs),
+        # stable, with three different arrival laws and unequal budgets
+        "stable": configs.known_classes(lam_per_class=(3.0, 3.5, 2.0), budgets=(4, 4, 3), n_replicas=8,
+                                        n_steps=1500, seed=21, **obs),
+        # a finite token budget and chunk: prompts take several slots and stall decodes
+        "chunked": configs.known_classes(lam_per_class=(0.3, 0.2, 0.25), budgets=(1, 1, 2),
+                                         lengths=((37, 5), (9, 30), (64, 1)), token_budget=48, prefill_chunk=16,
+                                         capacity=4000, n_replicas=8, n_steps=2000, seed=22, **obs),
+        # too small a memory: Algorithm 1 has no eviction, the overflowing slots are counted
+        "overflow": configs.known_classes(lam_per_class=(2.0, 2.0, 2.0), budgets=(2, 3, 2), capacity=300,
+                                          n_replicas=4, n_steps=800, seed=23, **obs),
+        # one class, and a class whose budget is zero (it only queues)
+        "one-class": configs.known_classes(lam_per_class=(1.5,), budgets=(2,), lengths=((12, 7),), capacity=2000,
+                                           n_replicas=4, n_steps=1000, seed=24, **obs),
+        "closed-class": configs.known_classes(lam_per_class=(1.0, 1.0), budgets=(0, 2), lengths=((5, 5), (8, 3)),
+                                              capacity=2000, n_replicas=4, n_steps=1000, seed=25, **obs),
+    }
+    for label, wl in cases.items():
+        eng = run(wl)
+        got, _, _ = compare(eng, wl, label=label)
+        check_summary(eng, wl, got)
+        assert not got["evictions"].any(), label
+        if label == "overflow":
+            assert got["overflow_steps"].sum() > 0 and np.any(got["max_u"] > wl.capacity)
+        if label == "chunked":
+            assert got["stalled"].sum() > 0
+        if label == "closed-class":
+            assert np.all(got["final_q"] > 0)
+
+
+def test_algorithm1_many_classes_and_slot_counts_not_a_multiple_of_the_window():
+    # 16 classes (the most the engine takes), T not a multiple of 64, and T below one window
+    lengths = tuple((1 + (7 * k) % 23, 1 + (5 * k) % 17) for k in range(16))
+    for T, seed in ((333, 31), (40, 32)):
+        wl = configs.known_classes(lam_per_class=(0.2,) * 16, budgets=(1,) * 16, lengths=lengths, capacity=5000,
+                                   n_replicas=3, n_steps=T, seed=seed, trace_every=10, hist_bins=256,
+                                   max_requests=4096)
+        compare(run(wl), wl, label=f"16 classes T={T}")
+
+
+def test_known_classes_full_size_sampled_paths():
+    # Section 4.1 under Algorithm 1 at 1,024 replicas x 10,000 slots, overloaded (printed rates) and stable
+    for rates, label in (((5.0, 5.0, 5.0), "known-classes full"), ((3.6, 3.6, 3.6), "known-classes stable full")):
+        wl = configs.known_classes(lam_per_class=rates)
+        eng, got = _full_size(wl, [0, 500, 1023], label)
+        assert eng.n_paths == 1024 and eng.n_steps == 10000
+        assert not got["evictions"].any() and not got["overflow_steps"].any()
+        assert np.all(got["max_u"] <= 16240)   # Theorem 1: U_t never exceeds the sum over classes of b_k w_k
+
+
 def test_repeated_launches_are_identical():
     # the kernel's pacing hints (wavefront priorities from a launch-wide mean pace) alternate between two
     # copies of their words from launch to launch; results must not depend on them
