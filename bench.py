@@ -25,14 +25,12 @@ BYTES_PER_REQUEST_STEP = 8.0
 HBM_PEAK_GBS = 8000.0
 
 
-def cpu_baseline(config_index: int, target_seconds: float = 15.0):
+def cpu_baseline(wl, target_seconds: float = 15.0):
     """Times the oracle as it stands on a bounded sample: a few replicas of every cell, full horizon."""
     import numpy as np
 
     import oracle
-    from workloads import configs
     cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")))
-    wl = configs.make(config_index, oracle.stability_bound)
     oracle.lib()
     # calibrate on one replica per cell, then size the sample for about target_seconds
     t0 = time.perf_counter()
@@ -84,6 +82,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=1, help="index of the benchmark configuration (default 1)")
+    ap.add_argument("--workload", choices=("known-classes",), default=None,
+                    help="instead of --config: the known-lengths study of Section 4.1 under Algorithm 1 "
+                         "(three classes, Poisson rate 5 and budget 4 each, M = 16492)")
     ap.add_argument("--replicas", type=int, default=None)
     ap.add_argument("--slots", type=int, default=None)
     ap.add_argument("--lds-slots", type=int, default=0)
@@ -106,12 +107,21 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no HIP device", file=sys.stderr)
         return 3
-    wl = configs.make(args.config, fcs.stability_bound)
-    if args.replicas or args.slots:
-        wl = wl.scaled(n_replicas=args.replicas, n_steps=args.slots)
-    if args.cells:
-        import dataclasses
-        wl = dataclasses.replace(wl, cells=tuple(wl.cells[int(i)] for i in args.cells.split(",")))
+    def build(bound):
+        """The workload; `bound` computes the stability bound that the budgets of the configurations use."""
+        w = configs.known_classes() if args.workload == "known-classes" else configs.make(args.config, bound)
+        if args.replicas or args.slots:
+            w = w.scaled(n_replicas=args.replicas, n_steps=args.slots)
+        if args.cells:
+            import dataclasses
+            w = dataclasses.replace(w, cells=tuple(w.cells[int(i)] for i in args.cells.split(",")))
+        return w
+
+    wl = build(fcs.stability_bound)
+    if args.workload == "known-classes":
+        wl_label, kernel = "known-classes", "fcs_sim_classes_kernel"
+    else:
+        wl_label, kernel = f"configs[{args.config}] {wl.name}", "fcs_sim_kernel"
     if args.copy_mib > 0:
         src = torch.ones(args.copy_mib << 20, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -146,7 +156,7 @@ def main() -> int:
         "value": value, "unit": "request-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "int32", "data": "synthetic",
-        "config": {"workload": f"configs[{args.config}] {wl.name}", "replicas": wl.n_replicas,
+        "config": {"workload": wl_label, "replicas": wl.n_replicas,
                    "slots": wl.n_steps, "cells": len(wl.cells), "paths": eng.n_paths,
                    "capacity": wl.capacity, "token_budget": wl.token_budget, "prefill_chunk": wl.prefill_chunk,
                    "request_steps_per_step": rs_per_step, "lds_slots": geo["lds_slots"],
@@ -154,12 +164,14 @@ def main() -> int:
                    "evictions": int(summary["evictions"]), "completed": int(summary["completed"])},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None if (args.cells or args.replicas or args.slots) else measured_traffic(args.config),
-                     "kernel": "fcs_sim_kernel", "kernel_ms": sum(kernel_ms) / len(kernel_ms),
+                     "traffic": None if (args.cells or args.replicas or args.slots or args.workload)
+                     else measured_traffic(args.config),
+                     "kernel": kernel, "kernel_ms": sum(kernel_ms) / len(kernel_ms),
                      "bytes_per_request_step": BYTES_PER_REQUEST_STEP},
     }
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(args.config)
+        import oracle
+        line["cpu_baseline"] = cpu_baseline(build(oracle.stability_bound))
     print(json.dumps(line))
     return 0
 
