@@ -62,9 +62,9 @@ struct KParams {
   fcs_outputs out;
 };
 
-// CLASSES cells keep two tables of 64 arrival counts per class in LDS (current window, and the
-// block the reader of each class queue stands in)
-inline int class_lds_words(int n_classes) { return 2 * kWave * n_classes; }
+// CLASSES cells keep three tables of 64 words per class in LDS (arrival counts of the current window,
+// cumulative counts of the block the reader of each class queue stands in, arrival-law thresholds)
+inline int class_lds_words(int n_classes) { return 3 * kWave * n_classes; }
 inline int lds_words(int lcap, int class_words) {
   return kLdsWordsPerSlot * lcap + S_NFIELDS * kStackLds + kScratchWords + class_words;
 }
