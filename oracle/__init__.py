@@ -9,6 +9,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
+import math
 import subprocess
 
 import numpy as np
@@ -46,6 +47,7 @@ class _Config(C.Structure):
         ("n_forced_B", C.c_int64), ("forced_B", C.POINTER(C.c_int32)),
         ("class_arrivals", C.POINTER(_Law)), ("class_budget", C.POINTER(C.c_int32)),
         ("forced_cls", C.POINTER(C.c_int32)),
+        ("protect_limit", C.c_int64),
     ]
 
 
@@ -73,6 +75,11 @@ def lib():
                                 C.c_uint64, C.c_int32, C.POINTER(_Outputs)]
         _lib.fo_invert.argtypes = [C.POINTER(_Law), C.POINTER(C.c_uint32), C.c_int64, C.POINTER(C.c_int64)]
     return _lib
+
+
+def protect_limit(alpha, capacity):
+    """Section 4.1, alpha-protection greedy: admission may fill (1 - alpha) M, here rounded down."""
+    return int(math.floor((1.0 - float(alpha)) * int(capacity)))
 
 
 def counter_names():
@@ -151,6 +158,8 @@ def run_cell(wl, cell_index, replica_ids=None, n_steps=None, seed=None, n_thread
     cfg.hist_shift = int(wl.hist_shift)
     cfg.max_requests = max_req
     cfg.n_forced = -1
+    if cell.policy == 3:
+        cfg.protect_limit = protect_limit(cell.alpha, wl.capacity)
     if cell.policy == 2:
         ca = (_Law * nc)(*[_law(wl.arrival_laws[a], keep) for a in cell.class_arrival])
         cb = np.ascontiguousarray(cell.class_budget, dtype=np.int32)

@@ -16,6 +16,9 @@
 //                     GREEDY: the b -> infinity limit described after Theorem 2, with the
 //                             "initial memory l+1" fit test of Section 4.1: move the head
 //                             while usage-after-this-slot + l + 1 <= M.
+//                     ALPHA : alpha-protection greedy baseline of Section 4.1: as GREEDY but
+//                             against (1 - alpha) M; on overflow (step 3) ALL active requests
+//                             go back to the waiting queue.
 //                     CLASSES: Algorithm 1 (known lengths): every class k has its own arrival
 //                             stream n_{t,k}, its own FIFO and an integer budget b_k; in
 //                             class order, min(b_k, |Q_k|) head requests of class k move
@@ -50,6 +53,9 @@
 // parity unpinned: the budget order of step 4, the provisioned-usage reading of
 // "Overflow" in step 3 and the front-of-queue re-entry are this build's readings of
 // passages the paper leaves open; they are pinned only by hand-computed trajectories.
+// The same holds for ALPHA's use of that provisioned usage in its fit test and for keeping the
+// prefill-first order of step 4 under it (Section 4.1 says it "prioritizes existing token jobs",
+// which the one-token-per-active-request slot model already does when no token budget binds).
 #include <algorithm>
 #include <atomic>
 #include <cstdint>
@@ -67,7 +73,7 @@ struct fo_law {
 };
 
 struct fo_config {
-  int32_t policy;  // 0 FLOW, 1 GREEDY, 2 CLASSES
+  int32_t policy;  // 0 FLOW, 1 GREEDY, 2 CLASSES, 3 ALPHA
   int32_t n_classes;
   int64_t capacity;
   int64_t token_budget;
@@ -94,6 +100,8 @@ struct fo_config {
   const fo_law* class_arrivals;  // n_classes laws of n_{t,k}
   const int32_t* class_budget;   // n_classes budgets b_k
   const int32_t* forced_cls;     // class of each forced arrival (with n_forced >= 0)
+  // ALPHA only
+  int64_t protect_limit;  // floor((1 - alpha) M): what admission may fill
 };
 
 enum {
@@ -323,9 +331,12 @@ void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, i
         ++activated;
       }
     } else {
+      // GREEDY fills the memory, ALPHA (Section 4.1, alpha-protection greedy) only its share
+      // (1 - alpha) M: the head moves while the usage with its initial memory l + 1 stays within it
+      const int64_t limit = cfg.policy == 3 ? cfg.protect_limit : M;
       while (!Q.empty()) {
         int64_t provisioned = usage(P) + static_cast<int64_t>(P.size());
-        if (provisioned + Q.front().l + 1 > M) break;
+        if (provisioned + Q.front().l + 1 > limit) break;
         activate_head();
       }
     }
@@ -333,7 +344,9 @@ void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, i
     // ---- 3. overflow: evict newest until the provisioned usage fits ---------
     bool overflowed = false;
     if (by_class && usage(P) + static_cast<int64_t>(P.size()) > M) overflowed = true;  // counted, nobody leaves
-    while (!by_class && usage(P) + static_cast<int64_t>(P.size()) > M) {
+    // (ALPHA: on overflow every active request goes back, newest first, so Q stays in arrival order)
+    const bool evict_all = cfg.policy == 3 && usage(P) + static_cast<int64_t>(P.size()) > M;
+    while (!by_class && (evict_all ? !P.empty() : usage(P) + static_cast<int64_t>(P.size()) > M)) {
       Request r = P.back();
       P.pop_back();
       r.p = 0;
@@ -471,7 +484,8 @@ int fo_invert(const fo_law* law, const uint32_t* u, int64_t n, int64_t* out) {
 int fo_run(const fo_config* cfg, int64_t n_ids, const int64_t* replica_ids, int64_t n_steps,
            uint64_t seed, int32_t n_threads, const fo_outputs* out) {
   if (!cfg || !out || !out->counters || n_ids < 0 || n_steps < 0) return -1;
-  if (cfg->policy < 0 || cfg->policy > 2) return -1;
+  if (cfg->policy < 0 || cfg->policy > 3) return -1;
+  if (cfg->policy == 3 && (cfg->protect_limit < 0 || cfg->protect_limit > cfg->capacity)) return -1;
   if (cfg->policy == 2) {
     if (!cfg->class_budget || (cfg->n_forced < 0 && !cfg->class_arrivals)) return -1;
     if (cfg->n_forced >= 0 && !cfg->forced_cls) return -1;

@@ -25,6 +25,7 @@ from .laws import Law, Mixture, RequestClass
 FLOW = 0     # Algorithm 2: rate-limited activation, LIFO eviction on overflow
 GREEDY = 1   # b -> infinity limit with a memory fit test: admit while it fits, evict newest
 CLASSES = 2  # Algorithm 1: known lengths, one FIFO, arrival stream and integer budget b_k per class
+ALPHA = 3    # alpha-protection greedy (Section 4.1): admit while it fits (1 - alpha) M, evict all on overflow
 
 
 @dataclasses.dataclass(frozen=True)
@@ -36,6 +37,7 @@ class Cell:
     label: str = ""
     class_arrival: tuple = ()   # CLASSES: per class, index into Workload.arrival_laws
     class_budget: tuple = ()    # CLASSES: per class, integer budget b_k
+    alpha: float = 0.0          # ALPHA: protected share of the memory
 
 
 @dataclasses.dataclass(frozen=True)
@@ -88,6 +90,12 @@ def flow_cell(arrival: int, b: float, label: str = "") -> Cell:
 
 def greedy_cell(arrival: int, label: str = "greedy") -> Cell:
     return Cell(GREEDY, arrival, 0, 0, label)
+
+
+def alpha_cell(arrival: int, alpha: float, label: str = "") -> Cell:
+    if not 0.0 <= alpha < 1.0:
+        raise ValueError("alpha in [0, 1)")
+    return Cell(ALPHA, arrival, 0, 0, label or f"alpha-protection({alpha:.6g})", alpha=float(alpha))
 
 
 def classes_cell(class_arrival, class_budget, label: str = "") -> Cell:
@@ -206,6 +214,20 @@ def known_classes(lam_per_class=(5.0, 5.0, 5.0), budgets=(4, 4, 4), lengths=((10
         name="known-classes", capacity=capacity, token_budget=token_budget, prefill_chunk=prefill_chunk,
         mixture=Mixture(cls), arrival_laws=arr, cells=(cell,), n_replicas=n_replicas, n_steps=n_steps,
         seed=seed, **kw)
+
+
+def alpha_sweep(alphas=(0.0, 0.1, 0.2, 0.3), lam_per_class: float = 3.0, capacity: int = 16492,
+                n_replicas: int = 1024, n_steps: int = 10_000, seed: int = 9, **kw) -> Workload:
+    """The paper's synthetic study with unknown types (Section 4.1) under the alpha-protection greedy
+    baseline, one cell per alpha (the paper searches a grid of alpha), plus the greedy / evict-newest
+    baseline on the same arrivals: classes (10, 20), (10, 40), (10, 60) in equal shares, Poisson arrivals."""
+    cls = tuple(RequestClass(1.0, laws.point(10), laws.point(o)) for o in (20, 40, 60))
+    cells = tuple(alpha_cell(0, a) for a in alphas) + (greedy_cell(0),)
+    return Workload(
+        name="alpha-sweep", capacity=capacity, token_budget=kw.pop("token_budget", 1 << 30),
+        prefill_chunk=kw.pop("prefill_chunk", 1 << 30), mixture=Mixture(cls),
+        arrival_laws=(laws.poisson_counts(3.0 * lam_per_class),), cells=cells, n_replicas=n_replicas,
+        n_steps=n_steps, seed=seed, **kw)
 
 
 def toy(capacity: int = 600, token_budget: int = 96, prefill_chunk: int = 32, lam: float = 0.6,
