@@ -82,9 +82,11 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=1, help="index of the benchmark configuration (default 1)")
-    ap.add_argument("--workload", choices=("known-classes",), default=None,
-                    help="instead of --config: the known-lengths study of Section 4.1 under Algorithm 1 "
-                         "(three classes, Poisson rate 5 and budget 4 each, M = 16492)")
+    ap.add_argument("--workload", choices=("known-classes", "alpha-sweep"), default=None,
+                    help="instead of --config: known-classes = the known-lengths study of Section 4.1 under "
+                         "Algorithm 1 (three classes, Poisson rate 5 and budget 4 each, M = 16492); alpha-sweep = "
+                         "the same three classes with unknown types under the alpha-protection greedy baseline "
+                         "for four values of alpha, and the greedy baseline")
     ap.add_argument("--replicas", type=int, default=None)
     ap.add_argument("--slots", type=int, default=None)
     ap.add_argument("--lds-slots", type=int, default=0)
@@ -109,7 +111,12 @@ def main() -> int:
         return 3
     def build(bound):
         """The workload; `bound` computes the stability bound that the budgets of the configurations use."""
-        w = configs.known_classes() if args.workload == "known-classes" else configs.make(args.config, bound)
+        if args.workload == "known-classes":
+            w = configs.known_classes()
+        elif args.workload == "alpha-sweep":
+            w = configs.alpha_sweep()
+        else:
+            w = configs.make(args.config, bound)
         if args.replicas or args.slots:
             w = w.scaled(n_replicas=args.replicas, n_steps=args.slots)
         if args.cells:
@@ -118,8 +125,8 @@ def main() -> int:
         return w
 
     wl = build(fcs.stability_bound)
-    if args.workload == "known-classes":
-        wl_label, kernel = "known-classes", "fcs_sim_classes_kernel"
+    if args.workload:
+        wl_label, kernel = args.workload, "fcs_sim_all_kernel"
     else:
         wl_label, kernel = f"configs[{args.config}] {wl.name}", "fcs_sim_kernel"
     if args.copy_mib > 0:

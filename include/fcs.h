@@ -19,8 +19,11 @@
  *      CLASSES (Algorithm 1): every class k of the length mixture has its own
  *      arrival stream n_{t,k}, its own FIFO queue and an integer budget b_k; in
  *      class order the first min(b_k, |Q_k|) requests of class k join P.
+ *      ALPHA (alpha-protection greedy baseline, Section 4.1): as GREEDY, against
+ *      protect_limit = (1 - alpha) M instead of M.
  *   3. overflow.  While (sum_P (l+j)) + |P| > M the most recently activated
  *      request is evicted: it loses its progress and returns to the FRONT of Q.
+ *      ALPHA: once that condition holds ALL active requests are evicted.
  *      CLASSES: Algorithm 1 has no such step (Theorem 1 keeps the usage below M
  *      when sum_k b_k w_k < M); the slots in which the condition holds are only
  *      counted in FCS_C_OVERFLOW_STEPS and the usage may exceed M.
@@ -75,7 +78,7 @@ enum {
   FCS_EDEVICE = -5    /* HIP error or no device                                   */
 };
 
-enum { FCS_POLICY_FLOW = 0, FCS_POLICY_GREEDY = 1, FCS_POLICY_CLASSES = 2 };
+enum { FCS_POLICY_FLOW = 0, FCS_POLICY_GREEDY = 1, FCS_POLICY_CLASSES = 2, FCS_POLICY_ALPHA = 3 };
 
 /* Integer law on {lo, ..., lo + n_thr}; thr non-decreasing (host pointer). */
 typedef struct fcs_law {
@@ -93,6 +96,7 @@ typedef struct fcs_cell {
   const int32_t* class_arrival; /* CLASSES: n_classes indices into fcs_params.arrival, */
                                 /*   the law of n_{t,k} of each class (host pointer)   */
   const int32_t* class_budget;  /* CLASSES: n_classes budgets b_k, 0 .. 64, sum <= 64  */
+  int32_t protect_limit;        /* ALPHA: (1 - alpha) M rounded down, 0 .. M           */
 } fcs_cell;
 
 typedef struct fcs_params {

@@ -9,6 +9,7 @@ without a GPU (so the exported symbols can be checked), but creating an
 from __future__ import annotations
 
 import ctypes as C
+import math
 import os
 
 import numpy as np
@@ -33,7 +34,8 @@ class fcs_law(C.Structure):
 class fcs_cell(C.Structure):
     _fields_ = [("policy", C.c_int32), ("arrival", C.c_int32), ("b_floor", C.c_int32),
                 ("b_frac_thr", C.c_uint32),
-                ("class_arrival", C.POINTER(C.c_int32)), ("class_budget", C.POINTER(C.c_int32))]
+                ("class_arrival", C.POINTER(C.c_int32)), ("class_budget", C.POINTER(C.c_int32)),
+                ("protect_limit", C.c_int32)]
 
 
 class fcs_params(C.Structure):
@@ -136,6 +138,8 @@ def make_params(wl, max_active: int = 0, lds_slots: int = 0):
     for i, c in enumerate(wl.cells):
         cells[i].policy, cells[i].arrival = int(c.policy), int(c.arrival)
         cells[i].b_floor, cells[i].b_frac_thr = int(c.b_floor), int(c.b_frac_thr)
+        if int(c.policy) == 3:  # alpha-protection greedy: admission may fill (1 - alpha) M, rounded down
+            cells[i].protect_limit = int(math.floor((1.0 - float(c.alpha)) * int(wl.capacity)))
         if getattr(c, "class_arrival", ()):  # per-class arrival laws and budgets (Algorithm 1)
             ca = np.ascontiguousarray(c.class_arrival, dtype=np.int32)
             cb = np.ascontiguousarray(c.class_budget, dtype=np.int32)

@@ -31,6 +31,7 @@ struct fcs_engine {
   int64_t spill_stride = 0;
   uint32_t launch_seq = 0;
   bool has_classes = false;
+  bool has_alpha = false;  // ALPHA cells: an overflow sends the whole active set to the evicted stack
   int64_t classes_active = 0;  // CLASSES: most requests active at once when no prefill ever waits
   size_t blob_bytes_padded = 0;
   // last run
@@ -76,7 +77,8 @@ bool params_ok(const fcs_params* p) {
   if (p->n_cells < 1 || !p->cells) return false;
   for (int32_t i = 0; i < p->n_cells; ++i) {
     const fcs_cell& c = p->cells[i];
-    if (c.policy != FCS_POLICY_FLOW && c.policy != FCS_POLICY_GREEDY && c.policy != FCS_POLICY_CLASSES) return false;
+    if (c.policy < FCS_POLICY_FLOW || c.policy > FCS_POLICY_ALPHA) return false;
+    if (c.policy == FCS_POLICY_ALPHA && (c.protect_limit < 0 || c.protect_limit > p->capacity)) return false;
     if (c.arrival < 0 || c.arrival >= p->n_arrival_laws) return false;
     if (c.b_floor < 0 || c.b_floor > 30000) return false;
     if (c.policy == FCS_POLICY_CLASSES) {  // Algorithm 1: known lengths, integer budgets
@@ -192,6 +194,7 @@ int fcs_create(const fcs_params* p, fcs_handle* out) {
   for (int32_t i = 0; i < p->n_cells; ++i) {
     DCell d{p->cells[i].policy, p->cells[i].arrival, p->cells[i].b_floor, p->cells[i].b_frac_thr};
     if (d.policy == FCS_POLICY_CLASSES) d.b_frac_thr = class_table_off[i];
+    if (d.policy == FCS_POLICY_ALPHA) { d.b_frac_thr = static_cast<uint32_t>(p->cells[i].protect_limit); h->has_alpha = true; }
     h->cells.push_back(d);
     std::memcpy(h->blob.data() + h->cells_off + 4 * i, &d, sizeof(d));
   }
@@ -225,7 +228,9 @@ static int geometry_for(fcs_engine* h, int64_t n_replicas, int32_t* lcap, int32_
   lc = static_cast<int32_t>(std::min<int64_t>(lc, static_cast<int64_t>(round_up(max_active, kLdsBlock))));
   *lcap = lc;
   *hcap = static_cast<int32_t>(std::max<int64_t>(max_active - lc, 0));
-  *hscap = static_cast<int32_t>(std::max<int64_t>(max_active - kStackLds, 0));
+  // the evicted stack holds what was evicted and not yet activated again; under ALPHA that can be a
+  // whole active set on top of the rest of an earlier one
+  *hscap = static_cast<int32_t>(std::max<int64_t>((h->has_alpha ? 2 : 1) * max_active - kStackLds, 0));
   return FCS_OK;
 }
 
@@ -287,6 +292,7 @@ int fcs_run_from(fcs_handle h, int64_t replica_base, int64_t n_replicas, int64_t
   kp.seed_hi = static_cast<uint32_t>(seed >> 32);
   kp.lcap = h->lcap; kp.hcap = h->hcap; kp.hscap = h->hscap;
   kp.class_words = h->has_classes ? class_lds_words(h->n_classes) : 0;
+  kp.all_policies = (h->has_classes || h->has_alpha) ? 1 : 0;
   kp.spill = reinterpret_cast<int32_t*>(static_cast<char*>(h->workspace) + h->blob_bytes_padded);
   kp.spill_stride = h->spill_stride;
   kp.trace_every = h->trace_every;

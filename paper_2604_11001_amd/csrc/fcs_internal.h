@@ -52,6 +52,7 @@ struct KParams {
   uint32_t seed_lo, seed_hi;
   int32_t lcap, hcap, hscap;  // LDS slots, spill slots, spill stack entries (per path)
   int32_t class_words;        // LDS words of the per-class tables (0 without CLASSES cells)
+  int32_t all_policies;       // some cell is neither FLOW nor GREEDY: run the kernel built with all policies
   int32_t* spill;             // per path: kSpillWordsPerSlot*hcap + S_NFIELDS*hscap words
   int64_t spill_stride;       // words per path
   int32_t trace_every, n_trace, hist_bins, hist_shift, max_requests;

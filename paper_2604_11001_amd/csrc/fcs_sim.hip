@@ -70,7 +70,7 @@ __device__ __forceinline__ int wrl_c(int s, int v) {
   asm("v_writelane_b32 %0, %1, %2" : "+v"(v) : "s"(s), "n"(l));
   return v;
 }
-#define wrl(s, l, v) wrl_c<l, FCS_WITH_CLASSES != 0>((s), (v))
+#define wrl(s, l, v) wrl_c<l, FCS_ALL_POLICIES != 0>((s), (v))
 
 // Lanes of the wavefront exchange data through LDS and the spill region (lane 0 writes a slot
 // that lane k reads later).  To the compiler each lane is a separate thread, so every such
@@ -141,23 +141,23 @@ __device__ __forceinline__ void st4(int32_t* p, v4i v) {
 enum { SL_SUM_U = 0, SL_SUM_P, SL_SUM_Q, SL_DEC_TOK, SL_ACT, SL_DONE, SL_EVICT, SL_OVF, SL_PF_TOK,
        SL_STALLED, SL_COUNT };
 
-#define FCS_WITH_CLASSES 0
+#define FCS_ALL_POLICIES 0
 #define FCS_KERNEL fcs_sim_kernel
 #include "fcs_sim_kernel.inc"
-#undef FCS_WITH_CLASSES
+#undef FCS_ALL_POLICIES
 #undef FCS_KERNEL
 
-#define FCS_WITH_CLASSES 1
-#define FCS_KERNEL fcs_sim_classes_kernel
+#define FCS_ALL_POLICIES 1
+#define FCS_KERNEL fcs_sim_all_kernel
 #include "fcs_sim_kernel.inc"
-#undef FCS_WITH_CLASSES
+#undef FCS_ALL_POLICIES
 #undef FCS_KERNEL
 
 }  // namespace
 
 int launch_sim(const KParams& kp, void* stream) {
   const size_t lds = static_cast<size_t>(lds_words(kp.lcap, kp.class_words)) * sizeof(int32_t);
-  void (*kernel)(const KParams) = kp.class_words > 0 ? fcs_sim_classes_kernel : fcs_sim_kernel;
+  void (*kernel)(const KParams) = kp.all_policies ? fcs_sim_all_kernel : fcs_sim_kernel;
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));

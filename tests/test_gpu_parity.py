@@ -9,7 +9,7 @@ import pytest
 import oracle
 import paper_2604_11001_amd as fcs
 from workloads import FLOW, GREEDY, configs, laws
-from workloads.configs import Workload, flow_cell, greedy_cell
+from workloads.configs import Workload, alpha_cell, flow_cell, greedy_cell
 
 from parity_util import check_summary, compare
 
@@ -240,6 +240,56 @@ def test_known_classes_full_size_sampled_paths():
         assert eng.n_paths == 1024 and eng.n_steps == 10000
         assert not got["evictions"].any() and not got["overflow_steps"].any()
         assert np.all(got["max_u"] <= 16240)   # Theorem 1: U_t never exceeds the sum over classes of b_k w_k
+
+
+# ---- alpha-protection greedy baseline (Section 4.1): fit test against (1 - alpha) M, evict all on overflow ----
+
+def test_alpha_protection_small_cases():
+    obs = dict(trace_every=10, hist_bins=256, max_requests=1 << 13)
+    mix = laws.single(laws.uniform_int(4, 60), laws.geometric(12.0, cap=80))
+    cells = (alpha_cell(0, 0.0), alpha_cell(0, 0.15), alpha_cell(0, 0.4), greedy_cell(0), flow_cell(0, 0.8))
+    cases = {
+        # chunked prompts and a binding token budget, overflows every few dozen slots
+        "toy": Workload(name="alpha-toy", capacity=600, token_budget=96, prefill_chunk=32, mixture=mix,
+                        arrival_laws=(laws.poisson_counts(0.6),), cells=cells, n_replicas=16, n_steps=1200,
+                        seed=51, **obs),
+        # the pure slot model (no chunking, no token budget)
+        "pure": Workload(name="alpha-pure", capacity=900, token_budget=INF, prefill_chunk=INF, mixture=mix,
+                         arrival_laws=(laws.poisson_counts(0.9),), cells=cells[:4], n_replicas=8, n_steps=1500,
+                         seed=52, **obs),
+        # hundreds of active requests: an overflow fills the LDS part of the evicted stack and goes on
+        # in the spill region
+        "big": Workload(name="alpha-big", capacity=6000, token_budget=600, prefill_chunk=64,
+                        mixture=laws.single(laws.uniform_int(1, 8), laws.geometric(40.0, cap=300)),
+                        arrival_laws=(laws.poisson_counts(2.6),),
+                        cells=(alpha_cell(0, 0.0), alpha_cell(0, 0.05), greedy_cell(0)), n_replicas=4,
+                        n_steps=2500, seed=53, trace_every=50, hist_bins=512, max_requests=1 << 15),
+    }
+    for label, wl in cases.items():
+        eng = run(wl)
+        got, _, _ = compare(eng, wl, label=label)
+        check_summary(eng, wl, got)
+        R = eng.n_replicas
+        assert got["overflow_steps"][:R].sum() > 0, label
+        # evict-all: far more evictions per overflow slot than the evict-newest baseline
+        if label == "big":
+            assert got["evictions"][:R].sum() > 64 * got["overflow_steps"][:R].sum()
+    # an engine with ALPHA cells and little LDS: the active set and the evicted stack use the spill tier
+    wl = cases["big"].scaled(n_replicas=2, n_steps=1500)
+    eng = run(wl, lds_slots=256, max_active=2048)
+    compare(eng, wl, label="big, spilled")
+
+
+def test_alpha_sweep_scaled_and_full_size_sampled_paths():
+    wl = configs.alpha_sweep(n_replicas=6, n_steps=3000, trace_every=100, hist_bins=512, max_requests=1 << 15)
+    got, _, _ = compare(run(wl), wl, label="alpha sweep scaled")
+    wl = configs.alpha_sweep()
+    eng, got = _full_size(wl, [0, 1023], "alpha sweep full", n_threads=16)
+    assert eng.n_paths == 5 * 1024 and eng.n_steps == 10000
+    R = eng.n_replicas
+    for i in (0, 2, 3):   # alpha = 0, 0.1, 0.15 overflow at this load: hundreds of requests go back at once
+        ov, ev = (int(got[k][i * R:(i + 1) * R].sum()) for k in ("overflow_steps", "evictions"))
+        assert ov > 0 and ev > 100 * ov, (i, ov, ev)
 
 
 def test_repeated_launches_are_identical():

@@ -216,7 +216,7 @@ def known_classes(lam_per_class=(5.0, 5.0, 5.0), budgets=(4, 4, 4), lengths=((10
         seed=seed, **kw)
 
 
-def alpha_sweep(alphas=(0.0, 0.1, 0.2, 0.3), lam_per_class: float = 3.0, capacity: int = 16492,
+def alpha_sweep(alphas=(0.0, 0.05, 0.1, 0.15), lam_per_class: float = 3.3, capacity: int = 16492,
                 n_replicas: int = 1024, n_steps: int = 10_000, seed: int = 9, **kw) -> Workload:
     """The paper's synthetic study with unknown types (Section 4.1) under the alpha-protection greedy
     baseline, one cell per alpha (the paper searches a grid of alpha), plus the greedy / evict-newest
