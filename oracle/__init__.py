@@ -48,6 +48,7 @@ class _Config(C.Structure):
         ("class_arrivals", C.POINTER(_Law)), ("class_budget", C.POINTER(C.c_int32)),
         ("forced_cls", C.POINTER(C.c_int32)),
         ("protect_limit", C.c_int64),
+        ("budget_mode", C.c_int32), ("reserved2", C.c_int32), ("budget_law", _Law), ("budget_b16", C.c_int64),
     ]
 
 
@@ -160,6 +161,12 @@ def run_cell(wl, cell_index, replica_ids=None, n_steps=None, seed=None, n_thread
     cfg.n_forced = -1
     if cell.policy == 3:
         cfg.protect_limit = protect_limit(cell.alpha, wl.capacity)
+    if cell.budget_law >= 0:
+        cfg.budget_mode = 1
+        cfg.budget_law = _law(wl.arrival_laws[cell.budget_law], keep)
+    elif cell.credit_b16 > 0:
+        cfg.budget_mode = 2
+        cfg.budget_b16 = int(cell.credit_b16)
     if cell.policy == 2:
         ca = (_Law * nc)(*[_law(wl.arrival_laws[a], keep) for a in cell.class_arrival])
         cb = np.ascontiguousarray(cell.class_budget, dtype=np.int32)

@@ -13,6 +13,9 @@
 // activation order):
 //   1. arrivals       Section 2.1: n_t requests join the tail of Q.
 //   2. admission      FLOW  : Algorithm 2, move min(B_t, |Q|) head requests to P, no fit test.
+//                             B_t: floor(b) + Bernoulli(b - floor(b)), or drawn from any bounded
+//                             integer law (both i.i.d. as Theorem 2 asks), or the deterministic
+//                             floor(t b) - floor((t - 1) b) of a credit accumulator.
 //                     GREEDY: the b -> infinity limit described after Theorem 2, with the
 //                             "initial memory l+1" fit test of Section 4.1: move the head
 //                             while usage-after-this-slot + l + 1 <= M.
@@ -102,6 +105,11 @@ struct fo_config {
   const int32_t* forced_cls;     // class of each forced arrival (with n_forced >= 0)
   // ALPHA only
   int64_t protect_limit;  // floor((1 - alpha) M): what admission may fill
+  // FLOW: how B_t is formed (Theorem 2 asks for i.i.d. bounded nonnegative integers with mean b)
+  int32_t budget_mode;    // 0: b_floor + Bernoulli; 1: drawn from budget_law; 2: credit accumulator
+  int32_t reserved2;
+  fo_law budget_law;      // mode 1: B_t = lo + #{thr <= word 1}
+  int64_t budget_b16;     // mode 2: b in units of 2^-16; B_t = floor(t b) - floor((t - 1) b)
 };
 
 enum {
@@ -324,7 +332,12 @@ void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, i
       if (cfg.n_forced_B > 0)
         B_t = cfg.forced_B[std::min<int64_t>(t, cfg.n_forced_B) - 1];
       else
-        B_t = cfg.b_floor + (blk[1] < cfg.b_frac_thr ? 1 : 0);
+        if (cfg.budget_mode == 1)  // any bounded law on the integers (Theorem 2)
+          B_t = invert(cfg.budget_law, blk[1]);
+        else if (cfg.budget_mode == 2)  // deterministic: the credit t b, spent in whole requests
+          B_t = ((static_cast<int64_t>(t) * cfg.budget_b16) >> 16) - ((static_cast<int64_t>(t - 1) * cfg.budget_b16) >> 16);
+        else
+          B_t = cfg.b_floor + (blk[1] < cfg.b_frac_thr ? 1 : 0);
       int64_t activated = 0;
       while (activated < B_t && !Q.empty()) {
         activate_head();
@@ -486,6 +499,8 @@ int fo_run(const fo_config* cfg, int64_t n_ids, const int64_t* replica_ids, int6
   if (!cfg || !out || !out->counters || n_ids < 0 || n_steps < 0) return -1;
   if (cfg->policy < 0 || cfg->policy > 3) return -1;
   if (cfg->policy == 3 && (cfg->protect_limit < 0 || cfg->protect_limit > cfg->capacity)) return -1;
+  if (cfg->budget_mode < 0 || cfg->budget_mode > 2 || (cfg->budget_mode != 0 && cfg->policy != 0)) return -1;
+  if (cfg->budget_mode == 2 && (cfg->budget_b16 < 0 || cfg->budget_b16 > (30000ll << 16))) return -1;
   if (cfg->policy == 2) {
     if (!cfg->class_budget || (cfg->n_forced < 0 && !cfg->class_arrivals)) return -1;
     if (cfg->n_forced >= 0 && !cfg->forced_cls) return -1;

@@ -38,6 +38,8 @@ class Cell:
     class_arrival: tuple = ()   # CLASSES: per class, index into Workload.arrival_laws
     class_budget: tuple = ()    # CLASSES: per class, integer budget b_k
     alpha: float = 0.0          # ALPHA: protected share of the memory
+    budget_law: int = -1        # FLOW, if >= 0: B_t is drawn from Workload.arrival_laws[budget_law]
+    credit_b16: int = 0         # FLOW, if > 0: B_t = floor(t b) - floor((t - 1) b), b = credit_b16 / 2^16
 
 
 @dataclasses.dataclass(frozen=True)
@@ -86,6 +88,19 @@ def default_b(lam: float, lam_star: float) -> float:
 def flow_cell(arrival: int, b: float, label: str = "") -> Cell:
     fl, th = split_b(b)
     return Cell(FLOW, arrival, fl, th, label or f"flow(b={b:.6g})")
+
+
+def flow_law_cell(arrival: int, budget_law: int, label: str = "") -> Cell:
+    """FLOW with B_t i.i.d. from a count law of the workload (Theorem 2: any bounded integer law)."""
+    return Cell(FLOW, arrival, 0, 0, label or f"flow(B~law {budget_law})", budget_law=int(budget_law))
+
+
+def flow_credit_cell(arrival: int, b: float, label: str = "") -> Cell:
+    """FLOW with the deterministic budget of a credit accumulator: floor(t b) - floor((t - 1) b)."""
+    b16 = int(round(b * 65536.0))
+    if b16 <= 0:
+        raise ValueError("b must be at least 2^-16")
+    return Cell(FLOW, arrival, 0, 0, label or f"flow(credit b={b16 / 65536.0:.6g})", credit_b16=b16)
 
 
 def greedy_cell(arrival: int, label: str = "greedy") -> Cell:
