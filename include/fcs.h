@@ -79,6 +79,7 @@ enum {
 };
 
 enum { FCS_POLICY_FLOW = 0, FCS_POLICY_GREEDY = 1, FCS_POLICY_CLASSES = 2, FCS_POLICY_ALPHA = 3 };
+enum { FCS_BUDGET_SPLIT = 0, FCS_BUDGET_LAW = 1, FCS_BUDGET_CREDIT = 2 };
 
 /* Integer law on {lo, ..., lo + n_thr}; thr non-decreasing (host pointer). */
 typedef struct fcs_law {
@@ -97,6 +98,15 @@ typedef struct fcs_cell {
                                 /*   the law of n_{t,k} of each class (host pointer)   */
   const int32_t* class_budget;  /* CLASSES: n_classes budgets b_k, 0 .. 64, sum <= 64  */
   int32_t protect_limit;        /* ALPHA: (1 - alpha) M rounded down, 0 .. M           */
+  int32_t budget_mode;          /* FLOW: how B_t is formed.  FCS_BUDGET_SPLIT (0): b_floor  */
+                                /*   + [u < b_frac_thr]; FCS_BUDGET_LAW: drawn from the     */
+                                /*   count law fcs_params.arrival[budget_law] (any bounded  */
+                                /*   integer law, Theorem 2; values <= 30000);              */
+                                /*   FCS_BUDGET_CREDIT: floor(t b) - floor((t - 1) b), the  */
+                                /*   deterministic budget of a credit accumulator, b =      */
+                                /*   budget_b16 / 65536 <= 30000                            */
+  int32_t budget_law;
+  uint32_t budget_b16;
 } fcs_cell;
 
 typedef struct fcs_params {

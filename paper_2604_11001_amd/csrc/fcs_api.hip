@@ -32,6 +32,7 @@ struct fcs_engine {
   uint32_t launch_seq = 0;
   bool has_classes = false;
   bool has_alpha = false;  // ALPHA cells: an overflow sends the whole active set to the evicted stack
+  bool has_budget_modes = false;  // FLOW cells whose B_t is not the Bernoulli split
   int64_t classes_active = 0;  // CLASSES: most requests active at once when no prefill ever waits
   size_t blob_bytes_padded = 0;
   // last run
@@ -79,6 +80,14 @@ bool params_ok(const fcs_params* p) {
     const fcs_cell& c = p->cells[i];
     if (c.policy < FCS_POLICY_FLOW || c.policy > FCS_POLICY_ALPHA) return false;
     if (c.policy == FCS_POLICY_ALPHA && (c.protect_limit < 0 || c.protect_limit > p->capacity)) return false;
+    if (c.budget_mode < FCS_BUDGET_SPLIT || c.budget_mode > FCS_BUDGET_CREDIT) return false;
+    if (c.budget_mode != FCS_BUDGET_SPLIT && c.policy != FCS_POLICY_FLOW) return false;
+    if (c.budget_mode == FCS_BUDGET_LAW) {
+      if (c.budget_law < 0 || c.budget_law >= p->n_arrival_laws) return false;
+      const fcs_law& bl = p->arrival[c.budget_law];
+      if (bl.lo < 0 || static_cast<int64_t>(bl.lo) + bl.n_thr > 30000) return false;
+    }
+    if (c.budget_mode == FCS_BUDGET_CREDIT && (c.budget_b16 == 0 || c.budget_b16 > (30000u << 16))) return false;
     if (c.arrival < 0 || c.arrival >= p->n_arrival_laws) return false;
     if (c.b_floor < 0 || c.b_floor > 30000) return false;
     if (c.policy == FCS_POLICY_CLASSES) {  // Algorithm 1: known lengths, integer budgets
@@ -195,6 +204,12 @@ int fcs_create(const fcs_params* p, fcs_handle* out) {
     DCell d{p->cells[i].policy, p->cells[i].arrival, p->cells[i].b_floor, p->cells[i].b_frac_thr};
     if (d.policy == FCS_POLICY_CLASSES) d.b_frac_thr = class_table_off[i];
     if (d.policy == FCS_POLICY_ALPHA) { d.b_frac_thr = static_cast<uint32_t>(p->cells[i].protect_limit); h->has_alpha = true; }
+    if (p->cells[i].budget_mode != FCS_BUDGET_SPLIT) {  // the mode rides in the bits above the policy
+      d.policy |= p->cells[i].budget_mode << 8;
+      if (p->cells[i].budget_mode == FCS_BUDGET_LAW) d.b_floor = p->cells[i].budget_law;
+      else d.b_frac_thr = p->cells[i].budget_b16;
+      h->has_budget_modes = true;
+    }
     h->cells.push_back(d);
     std::memcpy(h->blob.data() + h->cells_off + 4 * i, &d, sizeof(d));
   }
@@ -292,7 +307,7 @@ int fcs_run_from(fcs_handle h, int64_t replica_base, int64_t n_replicas, int64_t
   kp.seed_hi = static_cast<uint32_t>(seed >> 32);
   kp.lcap = h->lcap; kp.hcap = h->hcap; kp.hscap = h->hscap;
   kp.class_words = h->has_classes ? class_lds_words(h->n_classes) : 0;
-  kp.all_policies = (h->has_classes || h->has_alpha) ? 1 : 0;
+  kp.all_policies = (h->has_classes || h->has_alpha || h->has_budget_modes) ? 1 : 0;
   kp.spill = reinterpret_cast<int32_t*>(static_cast<char*>(h->workspace) + h->blob_bytes_padded);
   kp.spill_stride = h->spill_stride;
   kp.trace_every = h->trace_every;

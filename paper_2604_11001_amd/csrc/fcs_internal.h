@@ -19,10 +19,11 @@ struct DLaw {
 };
 
 struct DCell {
-  int32_t policy;
+  int32_t policy;       // bits 7:0 FCS_POLICY_*, bits 15:8 FCS_BUDGET_* (FLOW)
   int32_t arrival;
-  int32_t b_floor;
-  uint32_t b_frac_thr;  // CLASSES: word offset in the blob of {arrival law, budget} x n_classes
+  int32_t b_floor;      // FCS_BUDGET_LAW: index of the law of B_t
+  uint32_t b_frac_thr;  // CLASSES: word offset in the blob of {arrival law, budget} x n_classes;
+                        // ALPHA: (1 - alpha) M; FCS_BUDGET_CREDIT: b in units of 2^-16
 };
 
 // Words of one active-set slot: in LDS {END, footprint} pairs, PLEFT and the 4-word record; in the

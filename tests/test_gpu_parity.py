@@ -9,7 +9,7 @@ import pytest
 import oracle
 import paper_2604_11001_amd as fcs
 from workloads import FLOW, GREEDY, configs, laws
-from workloads.configs import Workload, alpha_cell, flow_cell, greedy_cell
+from workloads.configs import Workload, alpha_cell, flow_cell, flow_credit_cell, flow_law_cell, greedy_cell
 
 from parity_util import check_summary, compare
 
@@ -290,6 +290,29 @@ def test_alpha_sweep_scaled_and_full_size_sampled_paths():
     for i in (0, 2, 3):   # alpha = 0, 0.1, 0.15 overflow at this load: hundreds of requests go back at once
         ov, ev = (int(got[k][i * R:(i + 1) * R].sum()) for k in ("overflow_steps", "evictions"))
         assert ov > 0 and ev > 100 * ov, (i, ov, ev)
+
+
+# ---- other forms of B_t (Theorem 2: any bounded i.i.d. integer law; a deterministic credit accumulator) ----
+
+def test_budget_from_a_law_and_from_a_credit_accumulator():
+    budget_law = laws.from_pmf(0, np.array([0.15, 0.35, 0.2, 0.05, 0.25]))   # mean 1.9 on {0, ..., 4}
+    mix = laws.single(laws.uniform_int(4, 60), laws.geometric(12.0, cap=80))
+    cells = (flow_cell(0, 1.3), flow_law_cell(0, 1), flow_credit_cell(0, 1.25), flow_credit_cell(0, 0.3),
+             flow_law_cell(0, 2), greedy_cell(0))
+    wide = laws.from_pmf(0, np.ones(64) / 64.0)                               # 63 thresholds: the largest table
+    for label, M, lam, T in (("eviction-heavy", 600, 0.9, 1500), ("roomy", 20000, 1.1, 3000)):
+        wl = Workload(name="budget-" + label, capacity=M, token_budget=96, prefill_chunk=32, mixture=mix,
+                      arrival_laws=(laws.poisson_counts(lam), budget_law, wide), cells=cells, n_replicas=8,
+                      n_steps=T, seed=61, trace_every=10, hist_bins=256, max_requests=1 << 13)
+        eng = run(wl)
+        got, _, _ = compare(eng, wl, label=label)
+        check_summary(eng, wl, got)
+        R = eng.n_replicas
+        if label == "roomy":       # nothing binds: what is activated is what the budgets allow
+            assert not got["evictions"].any()
+            assert np.all(got["activations"][2 * R:3 * R] <= (T * 5) // 4)   # floor(T * 1.25) in total
+        else:
+            assert got["evictions"][:5 * R].sum() > 0
 
 
 def test_repeated_launches_are_identical():
