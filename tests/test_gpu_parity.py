@@ -315,6 +315,18 @@ def test_budget_from_a_law_and_from_a_credit_accumulator():
             assert got["evictions"][:5 * R].sum() > 0
 
 
+def test_budget_forms_scaled_and_full_size_sampled_paths():
+    wl = configs.budget_forms(oracle.stability_bound, n_replicas=8, n_steps=20000).scaled(
+        trace_every=500, hist_bins=1024, hist_shift=2, max_requests=1 << 15)
+    compare(run(wl), wl, label="budget forms scaled")
+    wl = configs.budget_forms(oracle.stability_bound)
+    eng, got = _full_size(wl, [0, 1023], "budget forms full")
+    assert eng.n_paths == 3 * 1024 and eng.n_steps == 100000
+    R = eng.n_replicas
+    act = got["activations"].astype(np.int64) - got["evictions"].astype(np.int64)   # first activations
+    assert np.all(act[2 * R:] <= int(100000 * wl.cells[2].credit_b16 / 65536))      # the credit bounds them
+
+
 def test_repeated_launches_are_identical():
     # the kernel's pacing hints (wavefront priorities from a launch-wide mean pace) alternate between two
     # copies of their words from launch to launch; results must not depend on them

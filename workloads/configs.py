@@ -231,6 +231,24 @@ def known_classes(lam_per_class=(5.0, 5.0, 5.0), budgets=(4, 4, 4), lengths=((10
         seed=seed, **kw)
 
 
+def budget_forms(bound: Bound, n_replicas: int = 1024, n_steps: int = 100_000) -> Workload:
+    """Configuration 1's workload under Algorithm 2 with three forms of the activation budget of the same
+    mean b: floor(b) + Bernoulli, a three-point law (Theorem 2 allows any bounded i.i.d. integer law), and
+    the deterministic credit accumulator."""
+    base = config1(bound)
+    lam_cell = base.cells[0]
+    b = lam_cell.b_floor + lam_cell.b_frac_thr / laws.TWO32
+    fl = int(math.floor(b))
+    frac = b - fl
+    # masses on {fl - 1, fl, fl + 1} (or {fl, fl + 1, fl + 2} when fl = 0) with mean b
+    lo = max(fl - 1, 0)
+    shift = b - (lo + 1)                   # mean relative to the middle point, in (-1, 1)
+    pmf = np.array([0.25 - shift / 2.0, 0.5, 0.25 + shift / 2.0])
+    cells = (lam_cell, flow_law_cell(0, 1, f"flow(B~3-point, mean {b:.6g})"), flow_credit_cell(0, b))
+    return dataclasses.replace(base, name="budget-forms", arrival_laws=base.arrival_laws + (laws.from_pmf(lo, pmf),),
+                               cells=cells, n_replicas=n_replicas, n_steps=n_steps, seed=10)
+
+
 def alpha_sweep(alphas=(0.0, 0.05, 0.1, 0.15), lam_per_class: float = 3.3, capacity: int = 16492,
                 n_replicas: int = 1024, n_steps: int = 10_000, seed: int = 9, **kw) -> Workload:
     """The paper's synthetic study with unknown types (Section 4.1) under the alpha-protection greedy
