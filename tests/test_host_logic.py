@@ -67,6 +67,33 @@ def test_create_validates_parameters():
     assert _create(ok.scaled(arrival_laws=(laws.uniform_int(0, 100),))) == -1            # > 63 thresholds
 
 
+def test_create_validates_the_other_policies():
+    import dataclasses
+    kc = configs.known_classes(n_replicas=2, n_steps=10)
+    assert _create(kc) == 0
+    cell = kc.cells[0]
+    with_cell = lambda **kw: kc.scaled(cells=(dataclasses.replace(cell, **kw),))
+    assert _create(with_cell(class_budget=(40, 20, 5))) == -1            # budgets sum to more than 64
+    assert _create(with_cell(class_budget=(4, -1, 4))) == -1
+    assert _create(with_cell(class_arrival=(0, 0, 9))) == -1             # no such arrival law
+    mixed = laws.Mixture((laws.RequestClass(1.0, laws.uniform_int(4, 9), laws.point(5)),) + kc.mixture.classes[1:])
+    assert _create(kc.scaled(mixture=mixed)) == -1                       # Algorithm 1 needs known lengths
+    # alpha-protection: the limit lies in [0, M]
+    al = configs.alpha_sweep(n_replicas=2, n_steps=10)
+    assert _create(al) == 0
+    p, keep = fcs.binding.make_params(al)
+    p.cells[0].protect_limit = al.capacity + 1
+    h = C.c_void_p()
+    assert fcs.lib().fcs_create(C.byref(p), C.byref(h)) == -1
+    # forms of B_t: only for FLOW cells, the law must exist, b in (0, 30000]
+    toy = configs.toy()
+    ok = toy.scaled(cells=(configs.flow_law_cell(0, 0), configs.flow_credit_cell(0, 1.5)))
+    assert _create(ok) == 0
+    assert _create(toy.scaled(cells=(configs.flow_law_cell(0, 5),))) == -1
+    assert _create(toy.scaled(cells=(dataclasses.replace(configs.greedy_cell(0), credit_b16=65536),))) == -1
+    assert _create(toy.scaled(cells=(dataclasses.replace(configs.flow_cell(0, 1.0), credit_b16=(30001 << 16)),))) == -1
+
+
 def test_calls_out_of_order_and_null_arguments():
     L = fcs.lib()
     p, keep = binding.make_params(configs.toy())
