@@ -92,6 +92,28 @@ def test_edge_cases():
     assert got["arrived"].min() > 64
 
 
+def test_edge_cases_of_the_other_policies():
+    obs = dict(trace_every=7, hist_bins=64, max_requests=256)
+    kc = lambda **kw: configs.known_classes(n_replicas=3, **obs, **kw)
+    cases = {
+        "classes, one slot": kc(n_steps=1),
+        "classes, all budgets zero": kc(n_steps=150, budgets=(0, 0, 0)),
+        "classes, no arrivals": kc(n_steps=150, lam_per_class=(0.0, 0.0, 0.0)),
+        "classes, memory for one request": kc(n_steps=300, lam_per_class=(0.2,), budgets=(1,), lengths=((5, 3),),
+                                              capacity=8),
+        "classes, budgets sum to 64": kc(n_steps=200, lam_per_class=(20.0, 20.0), budgets=(40, 24),
+                                         lengths=((2, 2), (3, 1)), capacity=4000),
+        "alpha, one slot": configs.alpha_sweep(n_replicas=3, n_steps=1, **obs),
+        "alpha, nothing may be admitted": configs.alpha_sweep(alphas=(0.9995,), n_replicas=3, n_steps=200, **obs),
+        "credit of 2^-16 per slot": configs.toy(n_replicas=3, n_steps=300).scaled(
+            cells=(flow_credit_cell(0, 2.0 ** -16), flow_credit_cell(0, 30000.0))),
+    }
+    for label, wl in cases.items():
+        got, _, _ = compare(run(wl), wl, label=label)
+        if "budgets zero" in label or "nothing may be admitted" in label:
+            assert not got["activations"][:3].any() and np.array_equal(got["arrived"][:3], got["final_q"][:3])
+
+
 def test_replica_base_shards_a_sweep():
     wl = configs.toy(n_replicas=8, n_steps=300)
     whole = run(wl)
