@@ -224,8 +224,12 @@ int fcs_run_from(fcs_handle h, int64_t replica_base, int64_t n_replicas, int64_t
 
 /* Waits for the last run, copies the per-path counters to host_counters
  * ([n_paths][FCS_N_COUNTERS], may be NULL) and fills the summary of one cell
- * (cell >= 0) or of all paths (cell = -1).  Returns FCS_EOVERFLOW if a path
- * stopped with an error (the summary still describes what was simulated). */
+ * (cell >= 0) or of all paths (cell = -1).  If a path stopped with an error
+ * the call returns the first such path's code, FCS_EOVERFLOW (it outgrew
+ * max_active or the evicted stack; raise max_active) or FCS_ESTATE (its state
+ * became inconsistent: a defect, not an input error); the counters and the
+ * summary still describe what was simulated, and summary->first_error_path
+ * and error_code name the path and its code. */
 int fcs_stats(fcs_handle h, int32_t cell, uint64_t* host_counters, fcs_summary* summary);
 
 /* Nearest-rank percentile num/den of the request latency of every path, from

@@ -390,7 +390,9 @@ int fcs_stats(fcs_handle h, int32_t cell, uint64_t* host_counters, fcs_summary* 
     s->first_error_path = first_err;
     s->error_code = err_code;
   }
-  return first_err >= 0 ? FCS_EOVERFLOW : FCS_OK;
+  // the first failing path's own code: FCS_EOVERFLOW (it outgrew a capacity) or FCS_ESTATE (its state
+  // became inconsistent, which no input should be able to cause)
+  return first_err >= 0 ? (err_code == FCS_ESTATE ? FCS_ESTATE : FCS_EOVERFLOW) : FCS_OK;
 }
 
 int fcs_percentile(fcs_handle h, int64_t num, int64_t den, int32_t* value, uint8_t* saturated) {
