@@ -118,7 +118,8 @@ typedef struct fcs_params {
   const fcs_law* prompt;  /* per class: law of l, lo >= 1                          */
   const fcs_law* decode;  /* per class: law of o, lo >= 1; max l + max o <= M      */
   int32_t n_arrival_laws;
-  const fcs_law* arrival; /* laws of n_t (lo = 0, at most 63 thresholds)           */
+  const fcs_law* arrival; /* count laws (at most 63 thresholds): of n_t and n_{t,k}, */
+                          /* which need lo = 0, and of B_t under FCS_BUDGET_LAW      */
   int32_t n_cells;
   const fcs_cell* cells;
   int32_t trace_every;    /* > 0: record (|Q_t|, U_t) at t = k, 2k, ...            */

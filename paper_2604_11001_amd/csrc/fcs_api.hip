@@ -74,7 +74,7 @@ bool params_ok(const fcs_params* p) {
   if (l_max + o_max > p->capacity) return false;
   if (p->n_arrival_laws < 1 || !p->arrival) return false;
   for (int32_t a = 0; a < p->n_arrival_laws; ++a)
-    if (!law_ok(p->arrival[a], 0, kMaxCountThr) || p->arrival[a].lo != 0) return false;
+    if (!law_ok(p->arrival[a], 0, kMaxCountThr)) return false;  // counts start at 0 where they are n_t (below)
   if (p->n_cells < 1 || !p->cells) return false;
   for (int32_t i = 0; i < p->n_cells; ++i) {
     const fcs_cell& c = p->cells[i];
@@ -88,7 +88,7 @@ bool params_ok(const fcs_params* p) {
       if (bl.lo < 0 || static_cast<int64_t>(bl.lo) + bl.n_thr > 30000) return false;
     }
     if (c.budget_mode == FCS_BUDGET_CREDIT && (c.budget_b16 == 0 || c.budget_b16 > (30000u << 16))) return false;
-    if (c.arrival < 0 || c.arrival >= p->n_arrival_laws) return false;
+    if (c.arrival < 0 || c.arrival >= p->n_arrival_laws || p->arrival[c.arrival].lo != 0) return false;
     if (c.b_floor < 0 || c.b_floor > 30000) return false;
     if (c.policy == FCS_POLICY_CLASSES) {  // Algorithm 1: known lengths, integer budgets
       if (!c.class_arrival || !c.class_budget) return false;
@@ -96,6 +96,7 @@ bool params_ok(const fcs_params* p) {
       for (int32_t k = 0; k < p->n_classes; ++k) {
         if (p->prompt[k].n_thr != 0 || p->decode[k].n_thr != 0) return false;
         if (c.class_arrival[k] < 0 || c.class_arrival[k] >= p->n_arrival_laws) return false;
+        if (p->arrival[c.class_arrival[k]].lo != 0) return false;
         if (c.class_budget[k] < 0 || c.class_budget[k] > kWave) return false;
         total += c.class_budget[k];
       }

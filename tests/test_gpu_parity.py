@@ -349,6 +349,53 @@ def test_budget_forms_scaled_and_full_size_sampled_paths():
     assert np.all(act[2 * R:] <= int(100000 * wl.cells[2].credit_b16 / 65536))      # the credit bounds them
 
 
+# ---- seeded random small workloads over every policy, budget form and tier ---------------------------------
+
+def _random_workload(rng, k):
+    obs = dict(trace_every=int(rng.integers(1, 40)), hist_bins=int(rng.choice([16, 200])),
+               hist_shift=int(rng.integers(0, 3)), max_requests=int(rng.choice([64, 4096])))
+    tau = INF if rng.random() < 0.3 else int(rng.integers(8, 200))
+    chunk = INF if rng.random() < 0.3 else int(rng.integers(2, 64))
+    T = int(rng.integers(60, 700))
+    if k % 3 == 2:   # Algorithm 1
+        m = int(rng.integers(1, 6))
+        lengths = tuple((int(rng.integers(1, 30)), int(rng.integers(1, 40))) for _ in range(m))
+        budgets = tuple(int(rng.integers(0, 4)) for _ in range(m))
+        rates = tuple(float(rng.choice([0.0, 0.3, 1.0, 2.5])) for _ in range(m))
+        need = max(l + o for l, o in lengths)
+        M = int(need + rng.integers(0, 3000))
+        return configs.known_classes(lam_per_class=rates, budgets=budgets, lengths=lengths, capacity=M,
+                                     token_budget=tau, prefill_chunk=chunk, n_replicas=3, n_steps=T,
+                                     seed=1000 + k, **obs), dict(max_active=4096)   # no eviction: a token
+        # budget that cannot keep up with the admitted prompts lets the active set grow with T
+    big = k % 6 == 4   # hundreds of active requests: evicted stack beyond LDS, prefill by prefix sums
+    l_hi = int(rng.integers(2, 12 if big else 60))
+    prompt = laws.uniform_int(int(rng.integers(1, l_hi)), l_hi)
+    o_cap = int(rng.integers(1, 120))
+    decode = laws.point(o_cap) if rng.random() < 0.2 else laws.geometric(float(rng.uniform(1.0, 30.0)), cap=o_cap)
+    M = int(l_hi + o_cap + rng.integers(0, 2500)) * (8 if big else 1)
+    lam = float(rng.uniform(3.0, 9.0) if big else rng.uniform(0.05, 2.5))
+    pmf = rng.random(int(rng.integers(2, 6)))
+    extra = laws.from_pmf(int(rng.integers(0, 2)), pmf / pmf.sum())
+    cells = (flow_cell(0, float(rng.uniform(0.1, 3.0))), greedy_cell(0), alpha_cell(0, float(rng.uniform(0.0, 0.6))),
+             flow_law_cell(0, 1), flow_credit_cell(0, float(rng.uniform(0.05, 3.0))))
+    wl = Workload(name=f"random-{k}", capacity=M, token_budget=tau, prefill_chunk=chunk,
+                  mixture=laws.single(prompt, decode), arrival_laws=(laws.poisson_counts(lam), extra), cells=cells,
+                  n_replicas=3, n_steps=T, seed=1000 + k, **obs)
+    small_lds = dict(lds_slots=256, max_active=4096) if rng.random() < 0.3 else {}
+    return wl, small_lds
+
+
+def test_random_small_workloads():
+    rng = np.random.default_rng(20260411)
+    for k in range(120):
+        wl, kw = _random_workload(rng, k)
+        eng = run(wl, **kw)
+        got, _, _ = compare(eng, wl, label=f"random workload {k}: {wl.name}, M={wl.capacity}, tau={wl.token_budget}, "
+                                           f"c={wl.prefill_chunk}, T={wl.n_steps}")
+        check_summary(eng, wl, got)
+
+
 def test_repeated_launches_are_identical():
     # the kernel's pacing hints (wavefront priorities from a launch-wide mean pace) alternate between two
     # copies of their words from launch to launch; results must not depend on them
