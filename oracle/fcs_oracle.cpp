@@ -54,7 +54,7 @@
 // uint32 threshold table: value = lo + #{i : u >= thr[i]}.
 //
 // parity unpinned: the budget order of step 4, the provisioned-usage reading of
-// "Overflow" in step 3 and the front-of-queue re-entry are this build's readings of
+// "Overflow" in step 3 and the front-of-queue re-entry are this oracle's readings of
 // passages the paper leaves open; they are pinned only by hand-computed trajectories.
 // The same holds for ALPHA's use of that provisioned usage in its fit test and for keeping the
 // prefill-first order of step 4 under it (Section 4.1 says it "prioritizes existing token jobs",
