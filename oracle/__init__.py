@@ -49,6 +49,7 @@ class _Config(C.Structure):
         ("forced_cls", C.POINTER(C.c_int32)),
         ("protect_limit", C.c_int64),
         ("budget_mode", C.c_int32), ("reserved2", C.c_int32), ("budget_law", _Law), ("budget_b16", C.c_int64),
+        ("assumed_o", C.c_int64),
     ]
 
 
@@ -161,6 +162,8 @@ def run_cell(wl, cell_index, replica_ids=None, n_steps=None, seed=None, n_thread
     cfg.n_forced = -1
     if cell.policy == 3:
         cfg.protect_limit = protect_limit(cell.alpha, wl.capacity)
+    if cell.policy == 4:
+        cfg.assumed_o = int(cell.assumed_o)
     if cell.budget_law >= 0:
         cfg.budget_mode = 1
         cfg.budget_law = _law(wl.arrival_laws[cell.budget_law], keep)

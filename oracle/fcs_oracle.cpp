@@ -22,6 +22,9 @@
 //                     ALPHA : alpha-protection greedy baseline of Section 4.1: as GREEDY but
 //                             against (1 - alpha) M; on overflow (step 3) ALL active requests
 //                             go back to the waiting queue.
+//                     MC    : memory-check benchmark of Section 4.1: first come first served, the
+//                             head moves only if the memory stays within M in every future slot
+//                             when all requests are taken to produce the longest possible output.
 //                     CLASSES: Algorithm 1 (known lengths): every class k has its own arrival
 //                             stream n_{t,k}, its own FIFO and an integer budget b_k; in
 //                             class order, min(b_k, |Q_k|) head requests of class k move
@@ -76,7 +79,7 @@ struct fo_law {
 };
 
 struct fo_config {
-  int32_t policy;  // 0 FLOW, 1 GREEDY, 2 CLASSES, 3 ALPHA
+  int32_t policy;  // 0 FLOW, 1 GREEDY, 2 CLASSES, 3 ALPHA, 4 MC
   int32_t n_classes;
   int64_t capacity;
   int64_t token_budget;
@@ -110,6 +113,8 @@ struct fo_config {
   int32_t reserved2;
   fo_law budget_law;      // mode 1: B_t = lo + #{thr <= word 1}
   int64_t budget_b16;     // mode 2: b in units of 2^-16; B_t = floor(t b) - floor((t - 1) b)
+  // MC only
+  int64_t assumed_o;      // output length every request is taken to reach in the prediction
 };
 
 enum {
@@ -343,6 +348,29 @@ void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, i
         activate_head();
         ++activated;
       }
+    } else if (cfg.policy == 4) {
+      // MC benchmark (Section 4.1): first come first served; the head moves only if, with it, the
+      // memory stays within M in every future slot of the prediction in which each request
+      // produces o_hat tokens, one per slot from the slot s of its first token (the slot in which it
+      // was, or is now, activated: no chunking and no token budget under this policy), holds
+      // l + (tokens so far) and leaves after its last one.  The usage only drops when somebody
+      // leaves, so the slots to look at are the last slots of the requests.
+      const int64_t o_hat = cfg.assumed_o;
+      auto fits_in_future = [&](const Request& c) {
+        struct Pred { int64_t l, s; };
+        std::vector<Pred> S;
+        for (const Request& r : P) S.push_back({r.l, t - r.j});  // j tokens by slot t - 1: the first came in t - j
+        S.push_back({c.l, t});
+        for (const Pred& k : S) {
+          const int64_t u = k.s + o_hat - 1;  // k's last slot
+          int64_t use = 0;
+          for (const Pred& i : S)
+            if (i.s + o_hat - 1 >= u) use += i.l + std::min(o_hat, u - i.s + 1);
+          if (use > M) return false;
+        }
+        return true;
+      };
+      while (!Q.empty() && fits_in_future(Q.front())) activate_head();
     } else {
       // GREEDY fills the memory, ALPHA (Section 4.1, alpha-protection greedy) only its share
       // (1 - alpha) M: the head moves while the usage with its initial memory l + 1 stays within it
@@ -497,7 +525,15 @@ int fo_invert(const fo_law* law, const uint32_t* u, int64_t n, int64_t* out) {
 int fo_run(const fo_config* cfg, int64_t n_ids, const int64_t* replica_ids, int64_t n_steps,
            uint64_t seed, int32_t n_threads, const fo_outputs* out) {
   if (!cfg || !out || !out->counters || n_ids < 0 || n_steps < 0) return -1;
-  if (cfg->policy < 0 || cfg->policy > 3) return -1;
+  if (cfg->policy < 0 || cfg->policy > 4) return -1;
+  if (cfg->policy == 4) {  // the prediction is that of the slot model without chunking or token budget
+    if (cfg->assumed_o < 1 || cfg->token_budget < (1ll << 30)) return -1;
+    for (int32_t k = 0; k < cfg->n_classes; ++k) {
+      if (cfg->prompt[k].lo + cfg->prompt[k].n_thr > cfg->prefill_chunk) return -1;
+      if (cfg->decode[k].lo + cfg->decode[k].n_thr > cfg->assumed_o) return -1;
+      if (cfg->prompt[k].lo + cfg->prompt[k].n_thr + cfg->assumed_o > cfg->capacity) return -1;
+    }
+  }
   if (cfg->policy == 3 && (cfg->protect_limit < 0 || cfg->protect_limit > cfg->capacity)) return -1;
   if (cfg->budget_mode < 0 || cfg->budget_mode > 2 || (cfg->budget_mode != 0 && cfg->policy != 0)) return -1;
   if (cfg->budget_mode == 2 && (cfg->budget_b16 < 0 || cfg->budget_b16 > (30000ll << 16))) return -1;

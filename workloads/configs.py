@@ -26,6 +26,7 @@ FLOW = 0     # Algorithm 2: rate-limited activation, LIFO eviction on overflow
 GREEDY = 1   # b -> infinity limit with a memory fit test: admit while it fits, evict newest
 CLASSES = 2  # Algorithm 1: known lengths, one FIFO, arrival stream and integer budget b_k per class
 ALPHA = 3    # alpha-protection greedy (Section 4.1): admit while it fits (1 - alpha) M, evict all on overflow
+MC = 4       # memory-check benchmark (Section 4.1): FCFS, admit only if the predicted future usage stays within M
 
 
 @dataclasses.dataclass(frozen=True)
@@ -40,6 +41,7 @@ class Cell:
     alpha: float = 0.0          # ALPHA: protected share of the memory
     budget_law: int = -1        # FLOW, if >= 0: B_t is drawn from Workload.arrival_laws[budget_law]
     credit_b16: int = 0         # FLOW, if > 0: B_t = floor(t b) - floor((t - 1) b), b = credit_b16 / 2^16
+    assumed_o: int = 0          # MC: output length every request is taken to reach (the longest possible one)
 
 
 @dataclasses.dataclass(frozen=True)
@@ -111,6 +113,16 @@ def alpha_cell(arrival: int, alpha: float, label: str = "") -> Cell:
     if not 0.0 <= alpha < 1.0:
         raise ValueError("alpha in [0, 1)")
     return Cell(ALPHA, arrival, 0, 0, label or f"alpha-protection({alpha:.6g})", alpha=float(alpha))
+
+
+def mc_cell(arrival: int, assumed_o: int, label: str = "") -> Cell:
+    """The memory-check benchmark with every output taken as `assumed_o` tokens long (Section 4.1: with
+    unknown types the longest possible value, `longest_output(mixture)`)."""
+    return Cell(MC, arrival, 0, 0, label or f"mc(o_hat={assumed_o})", assumed_o=int(assumed_o))
+
+
+def longest_output(mixture: Mixture) -> int:
+    return max(c.decode.hi for c in mixture.classes)
 
 
 def classes_cell(class_arrival, class_budget, label: str = "") -> Cell:
