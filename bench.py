@@ -82,12 +82,15 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=1, help="index of the benchmark configuration (default 1)")
-    ap.add_argument("--workload", choices=("known-classes", "alpha-sweep", "budget-forms"), default=None,
+    ap.add_argument("--workload", choices=("known-classes", "alpha-sweep", "budget-forms", "unknown-types"),
+                    default=None,
                     help="instead of --config: known-classes = the known-lengths study of Section 4.1 under "
                          "Algorithm 1 (three classes, Poisson rate 5 and budget 4 each, M = 16492); alpha-sweep = "
                          "the same three classes with unknown types under the alpha-protection greedy baseline "
                          "for four values of alpha, and the greedy baseline; budget-forms = the default "
-                         "workload under Algorithm 2 with three forms of the activation budget B_t")
+                         "workload under Algorithm 2 with three forms of the activation budget B_t; "
+                         "unknown-types = Section 4.1's three classes with unknown types under Algorithm 2, "
+                         "alpha-protection, the MC benchmark and greedy")
     ap.add_argument("--replicas", type=int, default=None)
     ap.add_argument("--slots", type=int, default=None)
     ap.add_argument("--lds-slots", type=int, default=0)
@@ -118,6 +121,8 @@ def main() -> int:
             w = configs.alpha_sweep()
         elif args.workload == "budget-forms":
             w = configs.budget_forms(bound)
+        elif args.workload == "unknown-types":
+            w = configs.unknown_types()
         else:
             w = configs.make(args.config, bound)
         if args.replicas or args.slots:

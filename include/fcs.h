@@ -21,6 +21,12 @@
  *      class order the first min(b_k, |Q_k|) requests of class k join P.
  *      ALPHA (alpha-protection greedy baseline, Section 4.1): as GREEDY, against
  *      protect_limit = (1 - alpha) M instead of M.
+ *      MC (memory-check benchmark, Section 4.1): first come first served, the
+ *      head joins P only if the memory stays within M in every future slot of the
+ *      prediction in which each request produces assumed_o tokens, one per slot
+ *      from the slot of its activation, holds l + (tokens so far) and leaves after
+ *      its last one.  Needs the slot model without chunking or token budget:
+ *      prefill_chunk >= largest l, token_budget = 2^30, largest l + assumed_o <= M.
  *   3. overflow.  While (sum_P (l+j)) + |P| > M the most recently activated
  *      request is evicted: it loses its progress and returns to the FRONT of Q.
  *      ALPHA: once that condition holds ALL active requests are evicted.
@@ -78,7 +84,8 @@ enum {
   FCS_EDEVICE = -5    /* HIP error or no device                                   */
 };
 
-enum { FCS_POLICY_FLOW = 0, FCS_POLICY_GREEDY = 1, FCS_POLICY_CLASSES = 2, FCS_POLICY_ALPHA = 3 };
+enum { FCS_POLICY_FLOW = 0, FCS_POLICY_GREEDY = 1, FCS_POLICY_CLASSES = 2, FCS_POLICY_ALPHA = 3,
+       FCS_POLICY_MC = 4 };
 enum { FCS_BUDGET_SPLIT = 0, FCS_BUDGET_LAW = 1, FCS_BUDGET_CREDIT = 2 };
 
 /* Integer law on {lo, ..., lo + n_thr}; thr non-decreasing (host pointer). */
@@ -107,6 +114,8 @@ typedef struct fcs_cell {
                                 /*   budget_b16 / 65536 <= 30000                            */
   int32_t budget_law;
   uint32_t budget_b16;
+  int32_t assumed_o;            /* MC: the output length o_hat every request is taken to    */
+                                /*   reach in the prediction, >= the largest o possible     */
 } fcs_cell;
 
 typedef struct fcs_params {

@@ -36,7 +36,7 @@ class fcs_cell(C.Structure):
                 ("b_frac_thr", C.c_uint32),
                 ("class_arrival", C.POINTER(C.c_int32)), ("class_budget", C.POINTER(C.c_int32)),
                 ("protect_limit", C.c_int32), ("budget_mode", C.c_int32), ("budget_law", C.c_int32),
-                ("budget_b16", C.c_uint32)]
+                ("budget_b16", C.c_uint32), ("assumed_o", C.c_int32)]
 
 
 class fcs_params(C.Structure):
@@ -143,6 +143,8 @@ def make_params(wl, max_active: int = 0, lds_slots: int = 0):
             cells[i].budget_mode, cells[i].budget_law = 1, int(c.budget_law)
         elif getattr(c, "credit_b16", 0) > 0:      # B_t of a credit accumulator
             cells[i].budget_mode, cells[i].budget_b16 = 2, int(c.credit_b16)
+        if int(c.policy) == 4:  # memory-check benchmark
+            cells[i].assumed_o = int(c.assumed_o)
         if int(c.policy) == 3:  # alpha-protection greedy: admission may fill (1 - alpha) M, rounded down
             cells[i].protect_limit = int(math.floor((1.0 - float(c.alpha)) * int(wl.capacity)))
         if getattr(c, "class_arrival", ()):  # per-class arrival laws and budgets (Algorithm 1)

@@ -33,6 +33,7 @@ struct fcs_engine {
   bool has_classes = false;
   bool has_alpha = false;  // ALPHA cells: an overflow sends the whole active set to the evicted stack
   bool has_budget_modes = false;  // FLOW cells whose B_t is not the Bernoulli split
+  bool has_mc = false;
   int64_t classes_active = 0;  // CLASSES: most requests active at once when no prefill ever waits
   size_t blob_bytes_padded = 0;
   // last run
@@ -78,7 +79,14 @@ bool params_ok(const fcs_params* p) {
   if (p->n_cells < 1 || !p->cells) return false;
   for (int32_t i = 0; i < p->n_cells; ++i) {
     const fcs_cell& c = p->cells[i];
-    if (c.policy < FCS_POLICY_FLOW || c.policy > FCS_POLICY_ALPHA) return false;
+    if (c.policy < FCS_POLICY_FLOW || c.policy > FCS_POLICY_MC) return false;
+    if (c.policy == FCS_POLICY_MC) {  // the prediction is that of the slot model without chunking or token budget
+      if (c.assumed_o < o_max || p->token_budget < kLimit || p->prefill_chunk < l_max) return false;
+      if (static_cast<int64_t>(l_max) + c.assumed_o > p->capacity) return false;
+      // the kernel sums l + j + o_hat over the active set in 32 bits
+      const int64_t most_active = p->max_active > 0 ? p->max_active : 8192;
+      if ((l_max + 2 * static_cast<int64_t>(c.assumed_o)) * most_active >= (1ll << 31)) return false;
+    }
     if (c.policy == FCS_POLICY_ALPHA && (c.protect_limit < 0 || c.protect_limit > p->capacity)) return false;
     if (c.budget_mode < FCS_BUDGET_SPLIT || c.budget_mode > FCS_BUDGET_CREDIT) return false;
     if (c.budget_mode != FCS_BUDGET_SPLIT && c.policy != FCS_POLICY_FLOW) return false;
@@ -204,6 +212,7 @@ int fcs_create(const fcs_params* p, fcs_handle* out) {
   for (int32_t i = 0; i < p->n_cells; ++i) {
     DCell d{p->cells[i].policy, p->cells[i].arrival, p->cells[i].b_floor, p->cells[i].b_frac_thr};
     if (d.policy == FCS_POLICY_CLASSES) d.b_frac_thr = class_table_off[i];
+    if (d.policy == FCS_POLICY_MC) { d.b_frac_thr = static_cast<uint32_t>(p->cells[i].assumed_o); h->has_mc = true; }
     if (d.policy == FCS_POLICY_ALPHA) { d.b_frac_thr = static_cast<uint32_t>(p->cells[i].protect_limit); h->has_alpha = true; }
     if (p->cells[i].budget_mode != FCS_BUDGET_SPLIT) {  // the mode rides in the bits above the policy
       d.policy |= p->cells[i].budget_mode << 8;
@@ -308,7 +317,7 @@ int fcs_run_from(fcs_handle h, int64_t replica_base, int64_t n_replicas, int64_t
   kp.seed_hi = static_cast<uint32_t>(seed >> 32);
   kp.lcap = h->lcap; kp.hcap = h->hcap; kp.hscap = h->hscap;
   kp.class_words = h->has_classes ? class_lds_words(h->n_classes) : 0;
-  kp.all_policies = (h->has_classes || h->has_alpha || h->has_budget_modes) ? 1 : 0;
+  kp.all_policies = (h->has_classes || h->has_alpha || h->has_budget_modes || h->has_mc) ? 1 : 0;
   kp.spill = reinterpret_cast<int32_t*>(static_cast<char*>(h->workspace) + h->blob_bytes_padded);
   kp.spill_stride = h->spill_stride;
   kp.trace_every = h->trace_every;

@@ -9,7 +9,8 @@ import pytest
 import oracle
 import paper_2604_11001_amd as fcs
 from workloads import FLOW, GREEDY, configs, laws
-from workloads.configs import Workload, alpha_cell, flow_cell, flow_credit_cell, flow_law_cell, greedy_cell
+from workloads.configs import (Workload, alpha_cell, flow_cell, flow_credit_cell, flow_law_cell, greedy_cell,
+                               longest_output, mc_cell)
 
 from parity_util import check_summary, compare
 
@@ -349,6 +350,57 @@ def test_budget_forms_scaled_and_full_size_sampled_paths():
     assert np.all(act[2 * R:] <= int(100000 * wl.cells[2].credit_b16 / 65536))      # the credit bounds them
 
 
+# ---- MC benchmark (Section 4.1): first come first served against a prediction of the future usage -------
+
+def test_mc_benchmark_cases():
+    obs = dict(trace_every=10, hist_bins=256, max_requests=1 << 14)
+    mix = laws.single(laws.uniform_int(4, 40), laws.geometric(20.0, cap=100))
+    two = laws.Mixture((laws.RequestClass(0.7, laws.uniform_int(2, 9), laws.geometric(8.0, cap=30)),
+                        laws.RequestClass(0.3, laws.uniform_int(20, 60), laws.uniform_int(50, 120))))
+    small = laws.single(laws.uniform_int(1, 6), laws.geometric(40.0, cap=150))
+    mk = lambda name, mixture, M, lam, T, cells, R=6: Workload(
+        name=name, capacity=M, token_budget=INF, prefill_chunk=INF, mixture=mixture,
+        arrival_laws=(laws.poisson_counts(lam),), cells=cells, n_replicas=R, n_steps=T, seed=71, **obs)
+    cases = {
+        "overloaded": mk("mc-over", mix, 1500, 2.0, 2000, (mc_cell(0, 100), greedy_cell(0))),
+        "loaded, three assumed lengths": mk("mc-assumed", mix, 2500, 1.6, 2000,
+                                            (mc_cell(0, 100), mc_cell(0, 200), mc_cell(0, 400))),
+        "exact lengths": mk("mc-exact", laws.single(laws.uniform_int(3, 12), laws.point(30)), 1200, 3.0, 1500,
+                            (mc_cell(0, 30),)),
+        "two classes": mk("mc-two", two, 5000, 1.2, 2500, (mc_cell(0, longest_output(two)), flow_cell(0, 1.5))),
+        "room for everybody": mk("mc-room", mix, 1 << 22, 1.5, 1000, (mc_cell(0, 100), greedy_cell(0))),
+        # hundreds of active requests: the prediction runs over several passes of 64 slots
+        "large active set": mk("mc-large", small, 45000, 9.0, 1500, (mc_cell(0, 150), mc_cell(0, 300)), R=3),
+        "memory for one request": mk("mc-one", laws.single(laws.uniform_int(2, 5), laws.uniform_int(1, 7)), 12, 0.4,
+                                     800, (mc_cell(0, 7),)),
+    }
+    for label, wl in cases.items():
+        eng = run(wl)
+        got, _, _ = compare(eng, wl, label=label)
+        check_summary(eng, wl, got)
+        R = eng.n_replicas
+        mc_rows = np.concatenate([np.arange(i * R, (i + 1) * R) for i, c in enumerate(wl.cells) if c.policy == 4])
+        assert not got["evictions"][mc_rows].any() and not got["overflow_steps"][mc_rows].any(), label
+        assert np.all(got["max_u"][mc_rows] <= wl.capacity), label
+        if label == "large active set":
+            assert got["max_p"][:R].min() > 200
+        if label == "room for everybody":
+            assert all(np.array_equal(got[k][:R], got[k][R:]) for k in got if k != "digest" or True)
+
+
+def test_unknown_types_scaled_and_full_size_sampled_paths():
+    # Section 4.1, unknown request types: Algorithm 2, alpha-protection, MC (longest output) and greedy
+    wl = configs.unknown_types(n_replicas=6, n_steps=3000, trace_every=100, hist_bins=1024, max_requests=1 << 15)
+    compare(run(wl), wl, label="unknown types scaled")
+    wl = configs.unknown_types()
+    eng, got = _full_size(wl, [0, 1023], "unknown types full", n_threads=16)
+    assert eng.n_paths == 4 * 1024 and eng.n_steps == 10000
+    R = eng.n_replicas
+    mc = slice(2 * R, 3 * R)
+    assert not got["evictions"][mc].any() and np.all(got["max_u"][mc] <= wl.capacity)
+    assert got["sum_q"][mc].sum() > 100 * got["sum_q"][:R].sum()    # the longest-length prediction admits too little
+
+
 # ---- seeded random small workloads over every policy, budget form and tier ---------------------------------
 
 def _random_workload(rng, k):
@@ -379,6 +431,9 @@ def _random_workload(rng, k):
     extra = laws.from_pmf(int(rng.integers(0, 2)), pmf / pmf.sum())
     cells = (flow_cell(0, float(rng.uniform(0.1, 3.0))), greedy_cell(0), alpha_cell(0, float(rng.uniform(0.0, 0.6))),
              flow_law_cell(0, 1), flow_credit_cell(0, float(rng.uniform(0.05, 3.0))))
+    if tau == INF and chunk >= l_hi:   # the MC benchmark is defined on the slot model without chunking or budget
+        cells += (mc_cell(0, decode.hi), mc_cell(0, decode.hi + int(rng.integers(1, 50))))
+        M = max(M, l_hi + cells[-1].assumed_o)
     wl = Workload(name=f"random-{k}", capacity=M, token_budget=tau, prefill_chunk=chunk,
                   mixture=laws.single(prompt, decode), arrival_laws=(laws.poisson_counts(lam), extra), cells=cells,
                   n_replicas=3, n_steps=T, seed=1000 + k, **obs)

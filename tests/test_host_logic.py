@@ -85,6 +85,13 @@ def test_create_validates_the_other_policies():
     p.cells[0].protect_limit = al.capacity + 1
     h = C.c_void_p()
     assert fcs.lib().fcs_create(C.byref(p), C.byref(h)) == -1
+    # MC benchmark: the slot model without chunking or token budget, an assumed length that covers every output
+    ut = configs.unknown_types(n_replicas=2, n_steps=10)
+    assert _create(ut) == 0
+    assert _create(ut.scaled(prefill_chunk=8)) == -1
+    assert _create(ut.scaled(token_budget=4096)) == -1
+    assert _create(ut.scaled(cells=(configs.mc_cell(0, 59),))) == -1     # a class produces 60 tokens
+    assert _create(ut.scaled(cells=(configs.mc_cell(0, 60),), capacity=69)) == -1
     # forms of B_t: only for FLOW cells, the law must exist, b in (0, 30000]
     toy = configs.toy()
     ok = toy.scaled(cells=(configs.flow_law_cell(0, 0), configs.flow_credit_cell(0, 1.5)))

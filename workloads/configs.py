@@ -275,6 +275,21 @@ def alpha_sweep(alphas=(0.0, 0.05, 0.1, 0.15), lam_per_class: float = 3.3, capac
         n_steps=n_steps, seed=seed, **kw)
 
 
+def unknown_types(lam_per_class: float = 3.3, b: float = 11.0, alpha: float = 0.05, capacity: int = 16492,
+                  n_replicas: int = 1024, n_steps: int = 10_000, seed: int = 12, **kw) -> Workload:
+    """The paper's synthetic study with unknown request types (Section 4.1, second row of its figure): classes
+    (10, 20), (10, 40), (10, 60) in equal shares, Poisson arrivals, M = 16492, under Algorithm 2, the
+    alpha-protection greedy baseline, the MC benchmark with the longest possible output (60), and the
+    greedy / evict-newest baseline, all on the same arrivals."""
+    cls = tuple(RequestClass(1.0, laws.point(10), laws.point(o)) for o in (20, 40, 60))
+    mix = Mixture(cls)
+    cells = (flow_cell(0, b), alpha_cell(0, alpha), mc_cell(0, longest_output(mix)), greedy_cell(0))
+    return Workload(
+        name="unknown-types", capacity=capacity, token_budget=1 << 30, prefill_chunk=1 << 30, mixture=mix,
+        arrival_laws=(laws.poisson_counts(3.0 * lam_per_class),), cells=cells, n_replicas=n_replicas,
+        n_steps=n_steps, seed=seed, **kw)
+
+
 def toy(capacity: int = 600, token_budget: int = 96, prefill_chunk: int = 32, lam: float = 0.6,
         b: float = 0.8, l_range=(4, 60), o_mean: float = 12.0, o_cap: int = 80,
         n_replicas: int = 16, n_steps: int = 400, seed: int = 11,
