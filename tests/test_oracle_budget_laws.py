@@ -81,3 +81,23 @@ def test_bernoulli_split_is_the_two_point_case_in_law():
     assert abs(ma - b) < 0.01 and abs(mc - b) < 0.01
     qa, qc = a["step_q"].mean(), c["step_q"].mean()
     assert abs(qa - qc) < 0.25 * max(qa, qc)
+
+
+def test_overflow_events_fall_as_the_memory_grows_at_a_fixed_margin():
+    # Theorem 2: with b E[w] <= (1 - eps) M the expected number of overflow events is below T exp(-C M^2).
+    # The constant is not given, so only the direction is checked: same eps and lambda / b, growing M
+    # (b and lambda grow with it), and a larger margin at one M.
+    mix = laws.single(laws.uniform_int(4, 40), laws.geometric(20.0, cap=120))
+    ew = oracle.expected_workload(mix)
+
+    def overflows(M, eps):
+        b = (1.0 - eps) * M / ew
+        wl = Workload(name="thm2", capacity=M, token_budget=INF, prefill_chunk=INF, mixture=mix,
+                      arrival_laws=(laws.poisson_counts(0.97 * b),), cells=(flow_cell(0, b),), n_replicas=16,
+                      n_steps=20000, seed=80)
+        return int(oracle.run_cell(wl, 0, n_threads=8)["counters"]["overflow_steps"].sum())
+
+    counts = [overflows(M, 0.1) for M in (1500, 3000, 6000, 12000)]
+    assert counts[0] > counts[1] > counts[2] > counts[3] > 0, counts
+    assert counts[3] < 0.2 * counts[0]
+    assert overflows(6000, 0.3) < 0.2 * counts[2]
