@@ -442,13 +442,20 @@ def _random_workload(rng, k):
 
 
 def test_random_small_workloads():
-    rng = np.random.default_rng(20260411)
-    for k in range(120):
-        wl, kw = _random_workload(rng, k)
-        eng = run(wl, **kw)
-        got, _, _ = compare(eng, wl, label=f"random workload {k}: {wl.name}, M={wl.capacity}, tau={wl.token_budget}, "
-                                           f"c={wl.prefill_chunk}, T={wl.n_steps}")
-        check_summary(eng, wl, got)
+    # FCS_PARITY_SEEDS="a:b" adds 30 workloads for each generator seed in [a, b) (a longer campaign by hand)
+    import os
+    runs = [(20260411, 120)]
+    if os.environ.get("FCS_PARITY_SEEDS"):
+        a, b = (int(v) for v in os.environ["FCS_PARITY_SEEDS"].split(":"))
+        runs += [(seed, 30) for seed in range(a, b)]
+    for seed, count in runs:
+        rng = np.random.default_rng(seed)
+        for k in range(count):
+            wl, kw = _random_workload(rng, k)
+            eng = run(wl, **kw)
+            got, _, _ = compare(eng, wl, label=f"random workload {seed}/{k}: {wl.name}, M={wl.capacity}, "
+                                               f"tau={wl.token_budget}, c={wl.prefill_chunk}, T={wl.n_steps}")
+            check_summary(eng, wl, got)
 
 
 def test_repeated_launches_are_identical():
