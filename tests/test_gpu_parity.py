@@ -414,7 +414,7 @@ def _random_workload(rng, k):
         lengths = tuple((int(rng.integers(1, 30)), int(rng.integers(1, 40))) for _ in range(m))
         budgets = tuple(int(rng.integers(0, 4)) for _ in range(m))
         rates = tuple(float(rng.choice([0.0, 0.3, 1.0, 2.5])) for _ in range(m))
-        need = max(l + o for l, o in lengths)
+        need = max(l for l, _ in lengths) + max(o for _, o in lengths)   # the engine asks for max l + max o <= M
         M = int(need + rng.integers(0, 3000))
         return configs.known_classes(lam_per_class=rates, budgets=budgets, lengths=lengths, capacity=M,
                                      token_budget=tau, prefill_chunk=chunk, n_replicas=3, n_steps=T,
@@ -448,14 +448,25 @@ def test_random_small_workloads():
     if os.environ.get("FCS_PARITY_SEEDS"):
         a, b = (int(v) for v in os.environ["FCS_PARITY_SEEDS"].split(":"))
         runs += [(seed, 30) for seed in range(a, b)]
+    done = outgrown = 0
     for seed, count in runs:
         rng = np.random.default_rng(seed)
         for k in range(count):
             wl, kw = _random_workload(rng, k)
             eng = run(wl, **kw)
-            got, _, _ = compare(eng, wl, label=f"random workload {seed}/{k}: {wl.name}, M={wl.capacity}, "
-                                               f"tau={wl.token_budget}, c={wl.prefill_chunk}, T={wl.n_steps}")
+            done += 1
+            try:
+                got, _, _ = compare(eng, wl, label=f"random workload {seed}/{k}: {wl.name}, M={wl.capacity}, "
+                                                   f"tau={wl.token_budget}, c={wl.prefill_chunk}, T={wl.n_steps}")
+            except fcs.FcsError as e:
+                # a random workload may outgrow the capacities the engine was given (an active set that
+                # only grows under Algorithm 1, a whole active set on the evicted stack): not a parity case
+                assert e.code == -4, (seed, k, e)
+                assert seed != 20260411, (k, e)     # none of the 120 standing cases does
+                outgrown += 1
+                continue
             check_summary(eng, wl, got)
+    assert outgrown <= done // 100, (outgrown, done)
 
 
 def test_repeated_launches_are_identical():
