@@ -167,7 +167,8 @@ enum {
   FCS_C_DIGEST,          /* FNV-1a (64-bit words) of the final state, see below     */
   FCS_C_ERROR,           /* 0, or -code of the error that stopped the path          */
   FCS_C_ERROR_STEP,      /* slot at which it stopped                                */
-  FCS_C_RESERVED,
+  FCS_C_ELAPSED,         /* time units the slots took (= n_steps while every slot   */
+                         /* lasts one unit)                                         */
   FCS_N_COUNTERS
 };
 /* Digest: h = 14695981039346656037; for each word x: h = (h ^ x) * 1099511628211.

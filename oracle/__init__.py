@@ -50,6 +50,7 @@ class _Config(C.Structure):
         ("protect_limit", C.c_int64),
         ("budget_mode", C.c_int32), ("reserved2", C.c_int32), ("budget_law", _Law), ("budget_b16", C.c_int64),
         ("assumed_o", C.c_int64),
+        ("time_c0", C.c_int64), ("time_cp", C.c_int64), ("time_cd", C.c_int64),
     ]
 
 
@@ -164,6 +165,7 @@ def run_cell(wl, cell_index, replica_ids=None, n_steps=None, seed=None, n_thread
         cfg.protect_limit = protect_limit(cell.alpha, wl.capacity)
     if cell.policy == 4:
         cfg.assumed_o = int(cell.assumed_o)
+    cfg.time_c0, cfg.time_cp, cfg.time_cd = (int(v) for v in getattr(wl, "time_model", (0, 0, 0)))
     if cell.budget_law >= 0:
         cfg.budget_mode = 1
         cfg.budget_law = _law(wl.arrival_laws[cell.budget_law], keep)

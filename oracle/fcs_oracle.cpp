@@ -117,6 +117,11 @@ struct fo_config {
   int64_t budget_b16;     // mode 2: b in units of 2^-16; B_t = floor(t b) - floor((t - 1) b)
   // MC only
   int64_t assumed_o;      // output length every request is taken to reach in the prediction
+  // Slots of variable duration (all three 0: every slot lasts one unit).  Time runs in units of the
+  // arrival law: n_u requests arrive in unit u; slot t starts at time tau_t (tau_1 = 1), sees the
+  // arrivals of the units up to tau_t, and lasts d_t = c0 + cp (prompt tokens it processed) + cd
+  // (output tokens it generated) units.
+  int64_t time_c0, time_cp, time_cd;
 };
 
 enum {
@@ -141,6 +146,7 @@ enum {
   FO_FINAL_Q,
   FO_FINAL_U,
   FO_DIGEST,
+  FO_ELAPSED,  // time units the T slots took (T when every slot lasts one unit)
   FO_N_COUNTERS
 };
 
@@ -238,6 +244,9 @@ void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, i
   const int64_t n_trace = cfg.trace_every > 0 ? T / cfg.trace_every : 0;
   int64_t next_id = 0;
   int64_t forced_pos = 0;
+  const bool timed = cfg.time_c0 != 0 || cfg.time_cp != 0 || cfg.time_cd != 0;
+  int64_t tau = 1;     // time at which the slot starts (= t while every slot lasts one unit)
+  int64_t u_seen = 0;  // arrivals of the units 1 .. u_seen have joined Q
   auto rec = [&](int32_t* arr, int64_t id, int64_t v) {
     if (arr && id < cfg.max_requests) arr[slot * cfg.max_requests + id] = static_cast<int32_t>(v);
   };
@@ -276,39 +285,50 @@ void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, i
           for (int64_t i = 0; i < n_tk; ++i) arrive(k);
         }
       }
-    } else if (cfg.n_forced >= 0) {
-      while (forced_pos < cfg.n_forced && cfg.forced_t[forced_pos] == t) {
-        Request r;
-        r.id = next_id++;
-        r.l = cfg.forced_l[forced_pos];
-        r.o = cfg.forced_o[forced_pos];
-        r.t_arr = t;
-        Q.push_back(r);
-        ++forced_pos;
-        ++n_t;
-      }
     } else {
-      n_t = invert(cfg.arrivals, blk[0]);
-      for (int64_t k = 0; k < n_t; ++k) {
-        const uint32_t ctr[4] = {static_cast<uint32_t>(k), static_cast<uint32_t>(t),
-                                 static_cast<uint32_t>(replica), 1u};
-        uint32_t w[4];
-        philox4x32_10(ctr, key, w);
-        fo_law cls_law{0, cfg.n_classes - 1, cfg.class_thr};
-        int64_t cls = invert(cls_law, w[0]);
-        Request r;
-        r.id = next_id++;
-        r.l = invert_sorted(cfg.prompt[cls], w[1]);
-        r.o = invert_sorted(cfg.decode[cls], w[2]);
-        r.t_arr = t;
-        Q.push_back(r);
-      }
-    }
-    for (int64_t k = 0; k < n_t && !by_class; ++k) {
-      const Request& r = Q[Q.size() - n_t + k];
-      rec(out.arrival_step, r.id, t);
-      rec(out.req_l, r.id, r.l);
-      rec(out.req_o, r.id, r.o);
+      // the arrivals of one time unit u join the tail of Q; a slot takes those of all units up to its start
+      auto arrivals_of = [&](int64_t u) {
+        int64_t n_u = 0;
+        if (cfg.n_forced >= 0) {
+          while (forced_pos < cfg.n_forced && cfg.forced_t[forced_pos] == u) {
+            Request r;
+            r.id = next_id++;
+            r.l = cfg.forced_l[forced_pos];
+            r.o = cfg.forced_o[forced_pos];
+            r.t_arr = u;
+            Q.push_back(r);
+            ++forced_pos;
+            ++n_u;
+          }
+        } else {
+          uint32_t bu[4];
+          const uint32_t cu[4] = {0u, static_cast<uint32_t>(u), static_cast<uint32_t>(replica), 0u};
+          philox4x32_10(cu, key, bu);
+          n_u = invert(cfg.arrivals, bu[0]);
+          for (int64_t k = 0; k < n_u; ++k) {
+            const uint32_t ctr[4] = {static_cast<uint32_t>(k), static_cast<uint32_t>(u),
+                                     static_cast<uint32_t>(replica), 1u};
+            uint32_t w[4];
+            philox4x32_10(ctr, key, w);
+            fo_law cls_law{0, cfg.n_classes - 1, cfg.class_thr};
+            int64_t cls = invert(cls_law, w[0]);
+            Request r;
+            r.id = next_id++;
+            r.l = invert_sorted(cfg.prompt[cls], w[1]);
+            r.o = invert_sorted(cfg.decode[cls], w[2]);
+            r.t_arr = u;
+            Q.push_back(r);
+          }
+        }
+        for (int64_t k = 0; k < n_u; ++k) {
+          const Request& r = Q[Q.size() - n_u + k];
+          rec(out.arrival_step, r.id, u);
+          rec(out.req_l, r.id, r.l);
+          rec(out.req_o, r.id, r.o);
+        }
+        return n_u;
+      };
+      while (u_seen < tau) n_t += arrivals_of(++u_seen);
     }
     C[FO_ARRIVED] += n_t;
 
@@ -319,8 +339,8 @@ void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, i
       Q.pop_front();
       r.p = 0;
       r.j = 0;
-      if (!r.was_active) rec(out.first_activation, r.id, t);
-      rec(out.last_activation, r.id, t);
+      if (!r.was_active) rec(out.first_activation, r.id, tau);
+      rec(out.last_activation, r.id, tau);
       r.was_active = true;
       P.push_back(r);
       C[FO_ACTIVATIONS] += 1;
@@ -402,6 +422,7 @@ void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, i
 
     // ---- 4. process: prefill chunks first, then one token per decoding request
     int64_t budget = cfg.token_budget;
+    const uint64_t pf_before = C[FO_PREFILL_TOKENS], dec_before = C[FO_DECODE_TOKENS];
     for (Request& r : P) r.decoding_at_slot_start = (r.p == r.l);
     for (Request& r : P) {
       if (r.p == r.l) continue;
@@ -448,16 +469,20 @@ void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, i
     if (out.step_b) out.step_b[slot * T + (t - 1)] = static_cast<int32_t>(B_t);
 
     // ---- 6. complete ---------------------------------------------------------
+    // the slot lasted d_t units; what completes in it does so in its last unit, tau + d_t - 1
+    const int64_t d_t = !timed ? 1
+                               : cfg.time_c0 + cfg.time_cp * static_cast<int64_t>(C[FO_PREFILL_TOKENS] - pf_before) +
+                                     cfg.time_cd * static_cast<int64_t>(C[FO_DECODE_TOKENS] - dec_before);
     std::vector<Request> keep;
     keep.reserve(P.size());
     for (const Request& r : P) {
       if (r.j == r.o) {
-        int64_t latency = t - r.t_arr + 1;
+        int64_t latency = tau + d_t - r.t_arr;  // both ends counted: t - t_arr + 1 in unit slots
         C[FO_COMPLETED] += 1;
         C[FO_SUM_LATENCY] += latency;
         C[FO_MAX_LATENCY] = std::max<uint64_t>(C[FO_MAX_LATENCY], latency);
         C[FO_USEFUL_TOKENS] += r.o;
-        rec(out.completion_step, r.id, t);
+        rec(out.completion_step, r.id, tau + d_t - 1);
         if (out.hist && cfg.hist_bins > 0) {
           int64_t b = std::min<int64_t>(latency >> cfg.hist_shift, cfg.hist_bins - 1);
           out.hist[slot * cfg.hist_bins + b] += 1;
@@ -467,7 +492,9 @@ void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, i
       }
     }
     P.swap(keep);
+    tau += d_t;
   }
+  C[FO_ELAPSED] = static_cast<uint64_t>(tau - 1);
 
   C[FO_FINAL_P] = P.size();
   C[FO_FINAL_Q] = Q.size();
@@ -505,7 +532,7 @@ const char* fo_counter_name(int i) {
       "completed", "arrived", "evictions", "activations", "sum_p", "sum_q", "sum_u",
       "overflow_steps", "sum_latency", "max_latency", "useful_tokens", "decode_tokens",
       "prefill_tokens", "stalled", "max_p", "max_q", "max_u", "final_p", "final_q",
-      "final_u", "digest"};
+      "final_u", "digest", "elapsed"};
   return (i >= 0 && i < FO_N_COUNTERS) ? names[i] : nullptr;
 }
 
@@ -538,6 +565,8 @@ int fo_run(const fo_config* cfg, int64_t n_ids, const int64_t* replica_ids, int6
   }
   if (cfg->policy == 3 && (cfg->protect_limit < 0 || cfg->protect_limit > cfg->capacity)) return -1;
   if (cfg->budget_mode < 0 || cfg->budget_mode > 2 || (cfg->budget_mode != 0 && cfg->policy != 0)) return -1;
+  if (cfg->time_c0 < 0 || cfg->time_cp < 0 || cfg->time_cd < 0) return -1;
+  if ((cfg->time_c0 != 0 || cfg->time_cp != 0 || cfg->time_cd != 0) && (cfg->time_c0 < 1 || cfg->policy == 2)) return -1;
   if (cfg->budget_mode == 2 && (cfg->budget_b16 < 0 || cfg->budget_b16 > (30000ll << 16))) return -1;
   if (cfg->policy == 2) {
     if (!cfg->class_budget || (cfg->n_forced < 0 && !cfg->class_arrivals)) return -1;

@@ -303,8 +303,6 @@ int fcs_run_from(fcs_handle h, int64_t replica_base, int64_t n_replicas, int64_t
   if (n_replicas < 1 || n_replicas > h->bound_replicas) return FCS_EINVAL;
   if (n_steps < 1 || n_steps >= kLimit) return FCS_EINVAL;
   if (replica_base < 0 || replica_base + n_replicas > 0xffffffffll) return FCS_EINVAL;
-  if (h->trace_every > 0 && (h->out.trace_q || h->out.trace_u) && n_steps / h->trace_every < 0)
-    return FCS_EINVAL;
   KParams kp{};
   kp.blob = static_cast<const uint32_t*>(h->workspace);
   kp.laws_off = h->laws_off; kp.cells_off = h->cells_off; kp.class_off = h->class_off;
@@ -493,7 +491,7 @@ const char* fcs_counter_name(int i) {
       "arrived", "activations", "completed", "evictions", "overflow_steps", "sum_u", "sum_p", "sum_q",
       "decode_tokens", "prefill_tokens", "useful_tokens", "stalled", "sum_latency", "max_latency",
       "max_u", "max_p", "max_q", "final_u", "final_p", "final_q", "digest", "error", "error_step",
-      "reserved"};
+      "elapsed"};
   return (i >= 0 && i < FCS_N_COUNTERS) ? names[i] : nullptr;
 }
 

@@ -60,6 +60,8 @@ class Workload:
     hist_bins: int = 0
     hist_shift: int = 0
     max_requests: int = 0      # per-path capacity of the per-request record arrays (0 = off)
+    time_model: tuple = (0, 0, 0)  # (c0, cp, cd): a slot lasts c0 + cp * prompt tokens + cd * output tokens
+                                   # time units, arrivals come per unit; all 0: every slot lasts one unit
     notes: str = ""
 
     def scaled(self, n_replicas: int | None = None, n_steps: int | None = None, **kw) -> "Workload":
