@@ -82,7 +82,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=1, help="index of the benchmark configuration (default 1)")
-    ap.add_argument("--workload", choices=("known-classes", "alpha-sweep", "budget-forms", "unknown-types"),
+    ap.add_argument("--workload", choices=("known-classes", "alpha-sweep", "budget-forms", "unknown-types",
+                                           "timed-study"),
                     default=None,
                     help="instead of --config: known-classes = the known-lengths study of Section 4.1 under "
                          "Algorithm 1 (three classes, Poisson rate 5 and budget 4 each, M = 16492); alpha-sweep = "
@@ -90,7 +91,8 @@ def main() -> int:
                          "for four values of alpha, and the greedy baseline; budget-forms = the default "
                          "workload under Algorithm 2 with three forms of the activation budget B_t; "
                          "unknown-types = Section 4.1's three classes with unknown types under Algorithm 2, "
-                         "alpha-protection, the MC benchmark and greedy")
+                         "alpha-protection, the MC benchmark and greedy; timed-study = configuration 1's "
+                         "mix under Algorithm 2 and greedy with slots of variable duration")
     ap.add_argument("--replicas", type=int, default=None)
     ap.add_argument("--slots", type=int, default=None)
     ap.add_argument("--lds-slots", type=int, default=0)
@@ -123,6 +125,8 @@ def main() -> int:
             w = configs.budget_forms(bound)
         elif args.workload == "unknown-types":
             w = configs.unknown_types()
+        elif args.workload == "timed-study":
+            w = configs.timed_study(bound)
         else:
             w = configs.make(args.config, bound)
         if args.replicas or args.slots:

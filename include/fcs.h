@@ -139,6 +139,15 @@ typedef struct fcs_params {
                            * M / (min l + 1) + 1, and with CLASSES cells at least
                            * sum_k b_k (ceil(l_k / min(c, tau)) + o_k + 1); at most 8192 */
   int32_t lds_slots;      /* active-set slots kept in LDS per path; 0 = automatic  */
+  /* Slots of variable duration (all three 0: every slot lasts one time unit).  Time runs
+   * in the units of the arrival laws: n_u requests arrive in unit u; slot t starts at time
+   * tau_t (tau_1 = 1), sees the arrivals of the units up to tau_t and lasts
+   * d_t = time_c0 + time_cp * (prompt tokens it processed) + time_cd * (output tokens it
+   * generated) units; a request completing in it does so in unit tau_t + d_t - 1.  Latencies,
+   * arrival_step and completion_step are then in time units and FCS_C_ELAPSED is the time
+   * the n_steps slots took.  time_c0 >= 1; not with CLASSES cells; n_steps times the
+   * longest possible d_t must stay below 2^30 (checked by fcs_run). */
+  int32_t time_c0, time_cp, time_cd;
 } fcs_params;
 
 /* Per-path counters, uint64 each, FCS_N_COUNTERS per path. */

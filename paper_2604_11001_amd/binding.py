@@ -48,6 +48,7 @@ class fcs_params(C.Structure):
         ("n_cells", C.c_int32), ("cells", C.POINTER(fcs_cell)),
         ("trace_every", C.c_int32), ("hist_bins", C.c_int32), ("hist_shift", C.c_int32),
         ("max_requests", C.c_int32), ("max_active", C.c_int32), ("lds_slots", C.c_int32),
+        ("time_c0", C.c_int32), ("time_cp", C.c_int32), ("time_cd", C.c_int32),
     ]
 
 
@@ -163,6 +164,7 @@ def make_params(wl, max_active: int = 0, lds_slots: int = 0):
     p.n_cells, p.cells = ncell, cells
     p.trace_every, p.hist_bins, p.hist_shift = int(wl.trace_every), int(wl.hist_bins), int(wl.hist_shift)
     p.max_requests, p.max_active, p.lds_slots = int(wl.max_requests), int(max_active), int(lds_slots)
+    p.time_c0, p.time_cp, p.time_cd = (int(v) for v in getattr(wl, "time_model", (0, 0, 0)))
     return p, keep
 
 

@@ -34,6 +34,7 @@ struct fcs_engine {
   bool has_alpha = false;  // ALPHA cells: an overflow sends the whole active set to the evicted stack
   bool has_budget_modes = false;  // FLOW cells whose B_t is not the Bernoulli split
   bool has_mc = false;
+  int32_t time_c0 = 0, time_cp = 0, time_cd = 0;
   int64_t classes_active = 0;  // CLASSES: most requests active at once when no prefill ever waits
   size_t blob_bytes_padded = 0;
   // last run
@@ -111,6 +112,12 @@ bool params_ok(const fcs_params* p) {
       if (total > kWave) return false;
     }
   }
+  if (p->time_c0 < 0 || p->time_cp < 0 || p->time_cd < 0) return false;
+  if (p->time_c0 != 0 || p->time_cp != 0 || p->time_cd != 0) {  // slots of variable duration
+    if (p->time_c0 < 1 || p->time_cp > (1 << 15) || p->time_cd > (1 << 15) || p->time_c0 > (1 << 20)) return false;
+    for (int32_t i = 0; i < p->n_cells; ++i)
+      if (p->cells[i].policy == FCS_POLICY_CLASSES) return false;
+  }
   if (p->trace_every < 0 || p->hist_bins < 0 || p->hist_bins > (1 << 24)) return false;
   if (p->hist_shift < 0 || p->hist_shift > 30 || p->max_requests < 0) return false;
   if (p->max_active < 0 || p->max_active > (1 << 24)) return false;
@@ -174,6 +181,7 @@ int fcs_create(const fcs_params* p, fcs_handle* out) {
   h->n_classes = p->n_classes; h->n_arrival_laws = p->n_arrival_laws; h->n_cells = p->n_cells;
   h->trace_every = p->trace_every; h->hist_bins = p->hist_bins; h->hist_shift = p->hist_shift;
   h->max_requests = p->max_requests; h->max_active = p->max_active; h->lds_slots_param = p->lds_slots;
+  h->time_c0 = p->time_c0; h->time_cp = p->time_cp; h->time_cd = p->time_cd;
   h->l_min = p->prompt[0].lo;
   for (int32_t c = 1; c < p->n_classes; ++c) h->l_min = std::min(h->l_min, p->prompt[c].lo);
 
@@ -315,7 +323,14 @@ int fcs_run_from(fcs_handle h, int64_t replica_base, int64_t n_replicas, int64_t
   kp.seed_hi = static_cast<uint32_t>(seed >> 32);
   kp.lcap = h->lcap; kp.hcap = h->hcap; kp.hscap = h->hscap;
   kp.class_words = h->has_classes ? class_lds_words(h->n_classes) : 0;
-  kp.all_policies = (h->has_classes || h->has_alpha || h->has_budget_modes || h->has_mc) ? 1 : 0;
+  kp.all_policies = (h->has_classes || h->has_alpha || h->has_budget_modes || h->has_mc || h->time_c0 != 0) ? 1 : 0;
+  kp.time_c0 = h->time_c0; kp.time_cp = h->time_cp; kp.time_cd = h->time_cd;
+  if (h->time_c0 != 0) {  // the clock of a path stays below 2^30
+    const int64_t most_active = static_cast<int64_t>(h->lcap) + h->hcap;
+    const int64_t d_max = h->time_c0 + static_cast<int64_t>(h->time_cp) * std::min<int64_t>(h->tau, h->M) +
+                          static_cast<int64_t>(h->time_cd) * std::min<int64_t>(h->tau, most_active);
+    if (n_steps * d_max >= kLimit) return FCS_EINVAL;
+  }
   kp.spill = reinterpret_cast<int32_t*>(static_cast<char*>(h->workspace) + h->blob_bytes_padded);
   kp.spill_stride = h->spill_stride;
   kp.trace_every = h->trace_every;

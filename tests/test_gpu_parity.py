@@ -388,6 +388,61 @@ def test_mc_benchmark_cases():
             assert all(np.array_equal(got[k][:R], got[k][R:]) for k in got if k != "digest" or True)
 
 
+# ---- slots of variable duration: d_t = c0 + cp (prompt tokens) + cd (output tokens) time units ------------
+
+def test_slots_of_variable_duration():
+    obs = dict(trace_every=10, hist_bins=512, hist_shift=1, max_requests=1 << 13)
+    mix = laws.single(laws.uniform_int(4, 60), laws.geometric(12.0, cap=80))
+    cells = (flow_cell(0, 0.8), greedy_cell(0), alpha_cell(0, 0.2), flow_credit_cell(0, 0.7))
+
+    def mk(time_model, lam, M=600, tau=96, chunk=32, T=1500, cs=cells, R=8):
+        return Workload(name=f"timed{time_model}", capacity=M, token_budget=tau, prefill_chunk=chunk, mixture=mix,
+                        arrival_laws=(laws.poisson_counts(lam),), cells=cs, n_replicas=R, n_steps=T, seed=91,
+                        time_model=time_model, **obs)
+
+    base = mk((0, 0, 0), 0.6)
+    ref_eng = run(base)
+    ref, _, _ = compare(ref_eng, base, label="unit slots, no time model")
+    # one unit per slot through the timed code: the same paths
+    unit = mk((1, 0, 0), 0.6)
+    eng = run(unit)
+    got, _, _ = compare(eng, unit, label="time model (1, 0, 0)")
+    for k in ref:
+        assert np.array_equal(ref[k], got[k]), k
+    assert np.all(got["elapsed"] == 1500)
+    assert np.array_equal(ref_eng.completion_step.cpu().numpy(), eng.completion_step.cpu().numpy())
+    for tm, lam in (((3, 1, 2), 0.02), ((1, 0, 1), 0.05), ((5, 0, 0), 0.1), ((2, 3, 0), 0.01), ((40, 1, 1), 0.01)):
+        wl = mk(tm, lam)
+        eng = run(wl)
+        got, _, _ = compare(eng, wl, label=f"time model {tm}")
+        check_summary(eng, wl, got)
+        want = 1500 * tm[0] + tm[1] * got["prefill_tokens"].astype(np.int64) + tm[2] * got["decode_tokens"].astype(np.int64)
+        assert np.array_equal(got["elapsed"].astype(np.int64), want), tm
+        assert got["evictions"].sum() > 0
+    # the pure slot model with the MC benchmark, little LDS (spill tier), a slot count below one window
+    pure = mk((2, 1, 1), 0.03, M=900, tau=INF, chunk=INF, cs=(mc_cell(0, 80), greedy_cell(0)), T=1200)
+    compare(run(pure), pure, label="timed, MC")
+    big = Workload(name="timed-big", capacity=6000, token_budget=600, prefill_chunk=64,
+                   mixture=laws.single(laws.uniform_int(1, 8), laws.geometric(40.0, cap=300)),
+                   arrival_laws=(laws.poisson_counts(0.05),), cells=(greedy_cell(0), alpha_cell(0, 0.05)),
+                   n_replicas=3, n_steps=1500, seed=92, time_model=(1, 1, 1), **obs)
+    compare(run(big, lds_slots=256, max_active=2048), big, label="timed, spilled")
+    short = mk((3, 1, 2), 0.02, T=40)
+    compare(run(short), short, label="timed, T = 40")
+
+
+def test_timed_study_scaled_and_full_size_sampled_paths():
+    wl = configs.timed_study(oracle.stability_bound, n_replicas=6, n_steps=4000).scaled(
+        trace_every=100, hist_bins=1024, hist_shift=6, max_requests=1 << 13)
+    compare(run(wl), wl, label="timed study scaled")
+    wl = configs.timed_study(oracle.stability_bound)
+    eng, got = _full_size(wl, [0, 1023], "timed study full")
+    assert eng.n_paths == 2048 and eng.n_steps == 10000
+    c0, cp, cd = wl.time_model
+    want = 10000 * c0 + cp * got["prefill_tokens"].astype(np.int64) + cd * got["decode_tokens"].astype(np.int64)
+    assert np.array_equal(got["elapsed"].astype(np.int64), want)
+
+
 def test_unknown_types_scaled_and_full_size_sampled_paths():
     # Section 4.1, unknown request types: Algorithm 2, alpha-protection, MC (longest output) and greedy
     wl = configs.unknown_types(n_replicas=6, n_steps=3000, trace_every=100, hist_bins=1024, max_requests=1 << 15)
@@ -434,9 +489,13 @@ def _random_workload(rng, k):
     if tau == INF and chunk >= l_hi:   # the MC benchmark is defined on the slot model without chunking or budget
         cells += (mc_cell(0, decode.hi), mc_cell(0, decode.hi + int(rng.integers(1, 50))))
         M = max(M, l_hi + cells[-1].assumed_o)
+    time_model = (0, 0, 0)
+    if k % 5 == 3:   # slots of variable duration; the arrival rate is per time unit, so it shrinks with them
+        time_model = (int(rng.integers(1, 6)), int(rng.integers(0, 3)), int(rng.integers(0, 3)))
+        lam = lam / (time_model[0] + 20.0 * time_model[1] + 10.0 * time_model[2])
     wl = Workload(name=f"random-{k}", capacity=M, token_budget=tau, prefill_chunk=chunk,
                   mixture=laws.single(prompt, decode), arrival_laws=(laws.poisson_counts(lam), extra), cells=cells,
-                  n_replicas=3, n_steps=T, seed=1000 + k, **obs)
+                  n_replicas=3, n_steps=T, seed=1000 + k, time_model=time_model, **obs)
     small_lds = dict(lds_slots=256, max_active=4096) if rng.random() < 0.3 else {}
     return wl, small_lds
 

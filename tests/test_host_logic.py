@@ -92,6 +92,12 @@ def test_create_validates_the_other_policies():
     assert _create(ut.scaled(token_budget=4096)) == -1
     assert _create(ut.scaled(cells=(configs.mc_cell(0, 59),))) == -1     # a class produces 60 tokens
     assert _create(ut.scaled(cells=(configs.mc_cell(0, 60),), capacity=69)) == -1
+    # slots of variable duration: c0 >= 1, not with Algorithm 1 cells
+    toy = configs.toy()
+    assert _create(toy.scaled(time_model=(2, 1, 1))) == 0
+    assert _create(toy.scaled(time_model=(0, 1, 1))) == -1
+    assert _create(toy.scaled(time_model=(1, -1, 0))) == -1
+    assert _create(kc.scaled(time_model=(1, 0, 0))) == -1
     # forms of B_t: only for FLOW cells, the law must exist, b in (0, 30000]
     toy = configs.toy()
     ok = toy.scaled(cells=(configs.flow_law_cell(0, 0), configs.flow_credit_cell(0, 1.5)))

@@ -292,6 +292,21 @@ def unknown_types(lam_per_class: float = 3.3, b: float = 11.0, alpha: float = 0.
         n_steps=n_steps, seed=seed, **kw)
 
 
+def timed_study(bound: Bound, time_model=(40, 1, 1), n_replicas: int = 1024, n_steps: int = 10_000) -> Workload:
+    """Configuration 1's request mix and memory under Algorithm 2 and the greedy baseline with slots of variable
+    duration (a linear stand-in for the batch times of Section 4.2): a slot lasts 40 + prompt tokens + output
+    tokens time units, requests arrive per unit at 0.9 of the rate the slot model would carry if every slot
+    took the duration of a typical one."""
+    base = config1(bound)
+    lam_slot = 0.9 * bound(base.mixture, base.capacity)              # per slot, as in configuration 1
+    typical = time_model[0] + time_model[1] * 300 + time_model[2] * 215  # prompt and output tokens of a typical slot
+    lam_unit = lam_slot / typical
+    b = default_b(lam_slot, bound(base.mixture, base.capacity))
+    return dataclasses.replace(base, name="timed-study", arrival_laws=(laws.poisson_counts(lam_unit),),
+                               cells=(flow_cell(0, b), greedy_cell(0)), n_replicas=n_replicas, n_steps=n_steps,
+                               seed=13, time_model=tuple(time_model))
+
+
 def toy(capacity: int = 600, token_budget: int = 96, prefill_chunk: int = 32, lam: float = 0.6,
         b: float = 0.8, l_range=(4, 60), o_mean: float = 12.0, o_cap: int = 80,
         n_replicas: int = 16, n_steps: int = 400, seed: int = 11,
