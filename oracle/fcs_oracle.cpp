@@ -62,6 +62,8 @@
 // The same holds for ALPHA's use of that provisioned usage in its fit test and for keeping the
 // prefill-first order of step 4 under it (Section 4.1 says it "prioritizes existing token jobs",
 // which the one-token-per-active-request slot model already does when no token budget binds).
+// Slots of variable duration (time_c0, time_cp, time_cd) are a linear stand-in for the batch times of
+// Section 4.2, which the paper takes from a simulator: the form is this oracle's choice.
 // The MC rule as a whole is a reading of one sentence of Section 4.1 (the rule comes from a cited
 // paper): usage checked in every future slot, all outputs taken as one common longest length.
 #include <algorithm>
