@@ -146,6 +146,14 @@ def main() -> int:
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
+        # the same copy timed: what a plain kernel reaches of the HBM peak on this device (read + written bytes)
+        cev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
+        for a, b in cev:
+            a.record()
+            dst.copy_(src)
+            b.record()
+        torch.cuda.synchronize()
+        copy_gbs = 2.0 * (args.copy_mib << 20) / (min(a.elapsed_time(b) for a, b in cev) * 1e-3) / 1e9
         del src, dst
     # statistics only: per-request records and histograms are parity-test outputs
     wl = wl.scaled(max_requests=0)
@@ -188,6 +196,8 @@ def main() -> int:
                      "kernel": kernel, "kernel_ms": sum(kernel_ms) / len(kernel_ms),
                      "bytes_per_request_step": BYTES_PER_REQUEST_STEP},
     }
+    if args.copy_mib > 0:
+        line["roofline"]["device_copy_gbs"] = copy_gbs
     if not args.no_cpu_baseline:
         import oracle
         line["cpu_baseline"] = cpu_baseline(build(oracle.stability_bound))
