@@ -177,6 +177,7 @@ int fcs_create(const fcs_params* p, fcs_handle* out) {
   if (!params_ok(p)) return FCS_EINVAL;
   fcs_engine* h = new (std::nothrow) fcs_engine();
   if (!h) return FCS_ENOMEM;
+  try {  // the tables are std::vectors: running out of host memory must not leave through the C boundary
   h->M = p->capacity; h->tau = p->token_budget; h->chunk = p->prefill_chunk;
   h->n_classes = p->n_classes; h->n_arrival_laws = p->n_arrival_laws; h->n_cells = p->n_cells;
   h->trace_every = p->trace_every; h->hist_bins = p->hist_bins; h->hist_shift = p->hist_shift;
@@ -234,6 +235,10 @@ int fcs_create(const fcs_params* p, fcs_handle* out) {
   for (int32_t c = 0; c + 1 < p->n_classes; ++c) h->blob[h->class_off + c] = p->class_thr[c];
   h->blob.insert(h->blob.end(), body.begin(), body.end());
   h->blob_bytes_padded = round_up(h->blob.size() * sizeof(uint32_t), 256);
+  } catch (const std::bad_alloc&) {
+    delete h;
+    return FCS_ENOMEM;
+  }
   *out = h;
   return FCS_OK;
 }
@@ -370,7 +375,11 @@ int fcs_stats(fcs_handle h, int32_t cell, uint64_t* host_counters, fcs_summary* 
   std::vector<uint64_t> local;
   uint64_t* C = host_counters;
   if (!C) {
-    local.resize(static_cast<size_t>(n_paths) * FCS_N_COUNTERS);
+    try {
+      local.resize(static_cast<size_t>(n_paths) * FCS_N_COUNTERS);
+    } catch (const std::bad_alloc&) {
+      return FCS_ENOMEM;
+    }
     C = local.data();
   }
   if (hipMemcpy(C, h->out.counters, sizeof(uint64_t) * n_paths * FCS_N_COUNTERS, hipMemcpyDeviceToHost) !=
@@ -426,7 +435,12 @@ int fcs_percentile(fcs_handle h, int64_t num, int64_t den, int32_t* value, uint8
   const int64_t n_paths = h->run_replicas * h->n_cells;
   const int64_t bins = h->hist_bins;
   const int64_t batch = std::max<int64_t>(1, (64ll << 20) / (bins * 4));
-  std::vector<uint32_t> buf(static_cast<size_t>(std::min(batch, n_paths) * bins));
+  std::vector<uint32_t> buf;
+  try {
+    buf.resize(static_cast<size_t>(std::min(batch, n_paths) * bins));
+  } catch (const std::bad_alloc&) {
+    return FCS_ENOMEM;
+  }
   for (int64_t p0 = 0; p0 < n_paths; p0 += batch) {
     const int64_t np = std::min(batch, n_paths - p0);
     if (hipMemcpy(buf.data(), h->out.hist + p0 * bins, sizeof(uint32_t) * np * bins, hipMemcpyDeviceToHost) !=
@@ -459,6 +473,7 @@ int fcs_stability_bound(const fcs_params* p, double* lambda_star) {
   if (!p || !lambda_star) return FCS_EINVAL;
   if (p->capacity < 1 || p->n_classes < 1 || p->n_classes > kMaxClasses || !p->prompt || !p->decode)
     return FCS_EINVAL;
+  if (p->n_classes > 1 && !p->class_thr) return FCS_EINVAL;
   const double two32 = 4294967296.0;
   double ew = 0.0, prev = 0.0;
   for (int32_t c = 0; c < p->n_classes; ++c) {
@@ -492,7 +507,7 @@ const char* fcs_strerror(int code) {
     case FCS_OK: return "ok";
     case FCS_EINVAL: return "invalid argument";
     case FCS_ENOMEM: return "workspace too small or out of host memory";
-    case FCS_ESTATE: return "call out of order";
+    case FCS_ESTATE: return "call out of order, or the state of a path became inconsistent";
     case FCS_EOVERFLOW: return "a path outgrew its active-set capacity";
     case FCS_EDEVICE: return "HIP error or no device";
     default: return "unknown error";

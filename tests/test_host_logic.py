@@ -120,6 +120,14 @@ def test_calls_out_of_order_and_null_arguments():
     assert L.fcs_create(None, C.byref(h)) == -1
     assert L.fcs_strerror(-4).decode().startswith("a path outgrew")
     L.fcs_destroy(h)
+    # a mixture of several classes without its class thresholds
+    p3, keep3 = binding.make_params(configs.three_class(1.0))
+    out = C.c_double(0.0)
+    assert L.fcs_stability_bound(C.byref(p3), C.byref(out)) == 0
+    p3.class_thr = None
+    assert L.fcs_stability_bound(C.byref(p3), C.byref(out)) == -1
+    assert L.fcs_create(C.byref(p3), C.byref(h)) == -1
+    assert L.fcs_stability_bound(C.byref(p3), None) == -1
 
 
 def test_engine_refuses_to_run_without_a_gpu():
