@@ -196,8 +196,13 @@ typedef struct fcs_outputs {
   uint32_t* hist;            /* [n_paths][hist_bins]                                */
   int32_t* arrival_step;     /* [n_paths][max_requests], 0 = no such request        */
   int32_t* completion_step;  /* [n_paths][max_requests], 0 = not completed          */
+  int64_t trace_entries;     /* int32 entries that trace_q and trace_u each hold    */
 } fcs_outputs;
-/* path = cell * n_replicas + replica. */
+/* path = cell * n_replicas + replica, n_paths = n_cells * n_replicas, with the
+ * n_replicas of fcs_bind for counters, hist, arrival_step and completion_step
+ * (a run of fewer replicas uses the leading rows).  The trace rows are packed
+ * by the run: n_replicas and n_steps are those of fcs_run, which refuses a run
+ * whose n_paths * (n_steps / trace_every) exceeds trace_entries. */
 
 typedef struct fcs_summary {
   int64_t n_paths;
@@ -235,7 +240,8 @@ int fcs_bind(fcs_handle h, void* dev_workspace, size_t bytes, int64_t n_replicas
 /* Simulates n_replicas sample paths per cell for slots 1..n_steps (Algorithm 2's
  * loop over t), replica r of every cell using Philox replica index
  * replica_base + r.  Asynchronous on stream; one workgroup of one wavefront per
- * path.  n_replicas must not exceed the bound value; 1 <= n_steps < 2^30. */
+ * path.  n_replicas must not exceed the bound value; 1 <= n_steps < 2^30;
+ * FCS_EINVAL also when the trace arrays are too short for the run. */
 int fcs_run(fcs_handle h, int64_t n_replicas, int64_t n_steps, uint64_t seed, void* stream);
 
 /* Same with an explicit first replica index (sharding a sweep over devices). */

@@ -54,7 +54,8 @@ class fcs_params(C.Structure):
 
 class fcs_outputs(C.Structure):
     _fields_ = [("counters", C.c_void_p), ("trace_q", C.c_void_p), ("trace_u", C.c_void_p),
-                ("hist", C.c_void_p), ("arrival_step", C.c_void_p), ("completion_step", C.c_void_p)]
+                ("hist", C.c_void_p), ("arrival_step", C.c_void_p), ("completion_step", C.c_void_p),
+                ("trace_entries", C.c_int64)]
 
 
 class fcs_summary(C.Structure):
@@ -213,6 +214,7 @@ class Engine:
                 self.trace_q = torch.zeros((self.n_paths, nt), dtype=torch.int32, device=dev)
                 self.trace_u = torch.zeros((self.n_paths, nt), dtype=torch.int32, device=dev)
                 self.out.trace_q, self.out.trace_u = self.trace_q.data_ptr(), self.trace_u.data_ptr()
+                self.out.trace_entries = self.trace_q.numel()
             if wl.hist_bins > 0:
                 self.hist = torch.zeros((self.n_paths, wl.hist_bins), dtype=torch.int32, device=dev)
                 self.out.hist = self.hist.data_ptr()

@@ -342,6 +342,9 @@ int fcs_run_from(fcs_handle h, int64_t replica_base, int64_t n_replicas, int64_t
   kp.n_trace = h->trace_every > 0 ? static_cast<int32_t>(n_steps / h->trace_every) : 0;
   kp.hist_bins = h->hist_bins; kp.hist_shift = h->hist_shift; kp.max_requests = h->max_requests;
   kp.n_paths = static_cast<int32_t>(n_replicas * h->n_cells);
+  if (h->trace_every > 0 && (h->out.trace_q || h->out.trace_u) &&
+      static_cast<int64_t>(kp.n_paths) * kp.n_trace > h->out.trace_entries)
+    return FCS_EINVAL;  // the caller's trace arrays are too short for this run
   {
     size_t need = 0;
     if (fcs_workspace_bytes(h, h->bound_replicas, &need) != FCS_OK) return FCS_ESTATE;

@@ -91,6 +91,15 @@ def test_edge_cases():
     short = configs.toy(n_replicas=2, n_steps=400, max_requests=64)
     got, _, _ = compare(run(short), short, label="short record arrays")
     assert got["arrived"].min() > 64
+    # a run longer than the trace arrays were sized for is refused, a shorter one is not
+    traced = configs.toy(n_replicas=2, n_steps=200).scaled(trace_every=10)
+    eng = fcs.Engine(traced)
+    with pytest.raises(fcs.FcsError) as e:
+        eng.run(n_steps=210)
+    assert e.value.code == -1
+    eng.run(n_steps=199)
+    eng.run()
+    compare(eng, traced, label="traces after a refused run")
 
 
 def test_edge_cases_of_the_other_policies():
