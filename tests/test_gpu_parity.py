@@ -102,6 +102,16 @@ def test_edge_cases():
     compare(eng, traced, label="traces after a refused run")
 
 
+def test_token_budget_about_the_size_of_the_active_set():
+    # the budget binds in most slots, for all or for part of the decoding requests, and their number
+    # crosses it back and forth: slots with and without prefill, with and without a budget test
+    for tau, chunk, lam, b in ((128, 48, 3.2, 4.0), (96, 40, 2.6, 3.0)):
+        wl = configs.toy(capacity=6000, token_budget=tau, prefill_chunk=chunk, lam=lam, b=b, o_mean=40.0, o_cap=200,
+                         l_range=(4, 30), n_replicas=6, n_steps=1500, max_requests=0)
+        got, _, _ = compare(run(wl), wl, label=f"tau={tau}")
+        assert got["stalled"].min() > 10 * wl.n_steps and got["max_p"].max() > tau
+
+
 def test_edge_cases_of_the_other_policies():
     obs = dict(trace_every=7, hist_bins=64, max_requests=256)
     kc = lambda **kw: configs.known_classes(n_replicas=3, **obs, **kw)
