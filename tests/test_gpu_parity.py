@@ -110,6 +110,11 @@ def test_token_budget_about_the_size_of_the_active_set():
                          l_range=(4, 30), n_replicas=6, n_steps=1500, max_requests=0)
         got, _, _ = compare(run(wl), wl, label=f"tau={tau}")
         assert got["stalled"].min() > 10 * wl.n_steps and got["max_p"].max() > tau
+    # the same with 300 to 480 active requests: both blocks of 256 slots hold decoding requests
+    wl = configs.toy(capacity=20000, token_budget=320, prefill_chunk=100, lam=6.0, b=7.0, o_mean=55.0, o_cap=240,
+                     l_range=(4, 40), n_replicas=6, n_steps=1500, max_requests=0)
+    got, _, _ = compare(run(wl), wl, label="tau=320")
+    assert got["stalled"].min() > 50 * wl.n_steps and got["max_p"].min() > 400
 
 
 def test_edge_cases_of_the_other_policies():
