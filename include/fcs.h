@@ -248,6 +248,22 @@ int fcs_run(fcs_handle h, int64_t n_replicas, int64_t n_steps, uint64_t seed, vo
 int fcs_run_from(fcs_handle h, int64_t replica_base, int64_t n_replicas, int64_t n_steps,
                  uint64_t seed, void* stream);
 
+/* For callers that cannot allocate device memory or pass a workspace around (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): fcs_bind and fcs_run in one call, on a
+ * workspace that the library itself holds on every GPU it is loaded on, FCS_STATIC_WORKSPACE_BYTES of
+ * device memory per GPU from load until the process ends.  The call allocates nothing.  dev_out are
+ * caller-owned device arrays as for fcs_bind, sized for this call's n_replicas; replica indices start at 0.
+ * FCS_ENOMEM when the tables plus the spill regions of n_replicas paths per cell (what
+ * fcs_workspace_bytes reports) exceed the workspace: lower n_replicas or fcs_params.max_active.
+ * The tables are uploaded when the workspace last held another engine's (that call waits for the
+ * stream once); otherwise the call only launches.  All calls on one GPU share the workspace: calls that
+ * overlap in time on one GPU race, whatever their streams; run them one after the other.  The current
+ * device at the time of the call is the one that is used.  fcs_stats, fcs_percentile and fcs_geometry
+ * afterwards refer to this run as they do after fcs_run. */
+#define FCS_STATIC_WORKSPACE_BYTES (32u << 20)
+int fcs_run_static(fcs_handle h, const fcs_outputs* dev_out, int64_t n_replicas, int64_t n_steps,
+                   uint64_t seed, void* stream);
+
 /* Waits for the last run, copies the per-path counters to host_counters
  * ([n_paths][FCS_N_COUNTERS], may be NULL) and fills the summary of one cell
  * (cell >= 0) or of all paths (cell = -1).  If a path stopped with an error
@@ -268,8 +284,8 @@ int fcs_percentile(fcs_handle h, int64_t num, int64_t den, int32_t* value, uint8
  * eq. 3), l and o independent within a class.  Host only. */
 int fcs_stability_bound(const fcs_params* params, double* lambda_star);
 
-/* Launch geometry chosen by fcs_bind: LDS slots per path, LDS bytes per workgroup,
- * spill slots per path. */
+/* Launch geometry of the last run, or before any run the one chosen by fcs_bind: LDS slots per path,
+ * LDS bytes per workgroup, spill slots per path. */
 int fcs_geometry(fcs_handle h, int32_t* lds_slots, int32_t* lds_bytes, int32_t* spill_slots);
 
 void fcs_destroy(fcs_handle h);

@@ -72,7 +72,7 @@ class fcs_summary(C.Structure):
         return {n: getattr(self, n) for n, _ in self._fields_ if n != "reserved"}
 
 
-EXPORTS = ["fcs_create", "fcs_workspace_bytes", "fcs_bind", "fcs_run", "fcs_run_from", "fcs_stats",
+EXPORTS = ["fcs_create", "fcs_workspace_bytes", "fcs_bind", "fcs_run", "fcs_run_from", "fcs_run_static", "fcs_stats",
            "fcs_percentile", "fcs_stability_bound", "fcs_geometry", "fcs_destroy", "fcs_strerror",
            "fcs_n_counters", "fcs_counter_name"]
 
@@ -92,6 +92,7 @@ def lib():
         L.fcs_bind.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int64, C.POINTER(fcs_outputs), C.c_void_p]
         L.fcs_run.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_uint64, C.c_void_p]
         L.fcs_run_from.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_uint64, C.c_void_p]
+        L.fcs_run_static.argtypes = [C.c_void_p, C.POINTER(fcs_outputs), C.c_int64, C.c_int64, C.c_uint64, C.c_void_p]
         L.fcs_stats.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(fcs_summary)]
         L.fcs_percentile.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]
         L.fcs_stability_bound.argtypes = [C.POINTER(fcs_params), C.POINTER(C.c_double)]
@@ -184,7 +185,10 @@ def stability_bound(mixture, capacity) -> float:
 class Engine:
     """Owns one fcs handle plus the torch device buffers bound to it."""
 
-    def __init__(self, wl, n_replicas=None, n_steps=None, device="cuda:0", max_active=0, lds_slots=0):
+    def __init__(self, wl, n_replicas=None, n_steps=None, device="cuda:0", max_active=0, lds_slots=0,
+                 static_workspace=False):
+        """static_workspace: no workspace is allocated or bound; ``run`` goes through fcs_run_static, on
+        the device memory that the library itself holds."""
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("libfcs needs a HIP device; there is no CPU fallback")
@@ -202,8 +206,9 @@ class Engine:
         nbytes = C.c_size_t(0)
         _check(lib().fcs_workspace_bytes(self._h, self.n_replicas, C.byref(nbytes)), "fcs_workspace_bytes")
         dev = self.device
+        self.static_workspace = bool(static_workspace)
         with torch.cuda.device(dev):
-            self.workspace = torch.empty(nbytes.value, dtype=torch.uint8, device=dev)
+            self.workspace = None if static_workspace else torch.empty(nbytes.value, dtype=torch.uint8, device=dev)
             nc = lib().fcs_n_counters()
             self.counters = torch.zeros((self.n_paths, nc), dtype=torch.int64, device=dev)
             self.out = fcs_outputs()
@@ -223,9 +228,10 @@ class Engine:
                 self.completion_step = torch.zeros_like(self.arrival_step)
                 self.out.arrival_step = self.arrival_step.data_ptr()
                 self.out.completion_step = self.completion_step.data_ptr()
-            stream = torch.cuda.current_stream(dev).cuda_stream
-            _check(lib().fcs_bind(self._h, self.workspace.data_ptr(), nbytes.value, self.n_replicas,
-                                  C.byref(self.out), C.c_void_p(stream)), "fcs_bind")
+            if not static_workspace:
+                stream = torch.cuda.current_stream(dev).cuda_stream
+                _check(lib().fcs_bind(self._h, self.workspace.data_ptr(), nbytes.value, self.n_replicas,
+                                      C.byref(self.out), C.c_void_p(stream)), "fcs_bind")
 
     def geometry(self):
         a, b, c = C.c_int32(), C.c_int32(), C.c_int32()
@@ -239,6 +245,11 @@ class Engine:
             stream = torch.cuda.current_stream(self.device).cuda_stream
         seed = int(self.wl.seed if seed is None else seed)
         T = int(self.n_steps if n_steps is None else n_steps)
+        if self.static_workspace:
+            with torch.cuda.device(self.device):
+                _check(lib().fcs_run_static(self._h, C.byref(self.out), self.n_replicas, T, seed, C.c_void_p(stream)),
+                       "fcs_run_static")
+            return
         _check(lib().fcs_run_from(self._h, int(replica_base), self.n_replicas, T, seed, C.c_void_p(stream)),
                "fcs_run_from")
 

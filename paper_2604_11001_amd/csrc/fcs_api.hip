@@ -4,7 +4,9 @@
 
 #include <algorithm>
 #include <cmath>
+#include <atomic>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -41,6 +43,9 @@ struct fcs_engine {
   bool ran = false;
   int64_t run_replicas = 0, run_steps = 0;
   void* run_stream = nullptr;
+  int32_t run_lcap = 0, run_hcap = 0;
+  fcs_outputs run_out{};  // the output arrays that run wrote (those of fcs_bind, or of fcs_run_static)
+  uint64_t uid = 0;       // distinguishes handles that follow each other at one address
 };
 
 namespace {
@@ -163,6 +168,29 @@ void law_moments(const fcs_law& L, double& m1, double& m2) {
   }
 }
 
+// ---- device memory of fcs_run_static ----------------------------------------------------------------
+// One array per GPU, there from the moment the library is loaded on that GPU until the process ends.
+// Host code never uses the array's name as an address: the per-device address comes from
+// hipGetSymbolAddress, once per device, and that pointer is what kernels, copies and fills receive.
+constexpr size_t kStaticBytes = static_cast<size_t>(FCS_STATIC_WORKSPACE_BYTES);
+constexpr size_t kStaticPaceOffset = kStaticBytes - 256;  // pacing words: the last 256 bytes
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+constexpr int kMaxDevices = 64;
+struct StaticSite {
+  void* ptr = nullptr;       // device address of `scratch` on this GPU
+  uint64_t blob_owner = 0;   // uid of the handle whose tables lie at the start of the array (0: none)
+  uint32_t launch_seq = 0;   // launches that used the array's pacing words
+};
+StaticSite g_static[kMaxDevices];
+std::mutex g_static_mu;
+std::atomic<uint64_t> g_next_uid{1};
+
+__global__ void fill_words_kernel(uint32_t* p, uint32_t v, int n) {
+  const int i = static_cast<int>(blockIdx.x * blockDim.x + threadIdx.x);
+  if (i < n) p[i] = v;
+}
+
 int sync_last(fcs_engine* h) {
   return hipStreamSynchronize(static_cast<hipStream_t>(h->run_stream)) == hipSuccess ? FCS_OK : FCS_EDEVICE;
 }
@@ -177,6 +205,7 @@ int fcs_create(const fcs_params* p, fcs_handle* out) {
   if (!params_ok(p)) return FCS_EINVAL;
   fcs_engine* h = new (std::nothrow) fcs_engine();
   if (!h) return FCS_ENOMEM;
+  h->uid = g_next_uid.fetch_add(1);
   try {  // the tables are std::vectors: running out of host memory must not leave through the C boundary
   h->M = p->capacity; h->tau = p->token_budget; h->chunk = p->prefill_chunk;
   h->n_classes = p->n_classes; h->n_arrival_laws = p->n_arrival_laws; h->n_cells = p->n_cells;
@@ -309,15 +338,23 @@ int fcs_bind(fcs_handle h, void* ws, size_t bytes, int64_t n_replicas, const fcs
   return FCS_OK;
 }
 
-int fcs_run_from(fcs_handle h, int64_t replica_base, int64_t n_replicas, int64_t n_steps, uint64_t seed,
-                 void* stream) {
-  if (!h) return FCS_EINVAL;
-  if (!h->bound) return FCS_ESTATE;
-  if (n_replicas < 1 || n_replicas > h->bound_replicas) return FCS_EINVAL;
+// Where a launch finds its device memory: the workspace (table blob, then the spill regions), the pacing
+// words, the output arrays, and the geometry the spill regions were laid out for.
+struct LaunchSite {
+  void* workspace;
+  unsigned long long* pace;
+  uint32_t launch_seq;
+  fcs_outputs out;
+  int32_t lcap, hcap, hscap;
+  int64_t spill_stride;
+};
+
+static int run_on(fcs_engine* h, const LaunchSite& site, int64_t replica_base, int64_t n_replicas, int64_t n_steps,
+                  uint64_t seed, void* stream) {
   if (n_steps < 1 || n_steps >= kLimit) return FCS_EINVAL;
   if (replica_base < 0 || replica_base + n_replicas > 0xffffffffll) return FCS_EINVAL;
   KParams kp{};
-  kp.blob = static_cast<const uint32_t*>(h->workspace);
+  kp.blob = static_cast<const uint32_t*>(site.workspace);
   kp.laws_off = h->laws_off; kp.cells_off = h->cells_off; kp.class_off = h->class_off;
   kp.n_arrival_laws = h->n_arrival_laws; kp.n_classes = h->n_classes; kp.n_cells = h->n_cells;
   kp.M = h->M; kp.tau = h->tau; kp.chunk = h->chunk;
@@ -326,32 +363,28 @@ int fcs_run_from(fcs_handle h, int64_t replica_base, int64_t n_replicas, int64_t
   kp.n_steps = static_cast<int32_t>(n_steps);
   kp.seed_lo = static_cast<uint32_t>(seed);
   kp.seed_hi = static_cast<uint32_t>(seed >> 32);
-  kp.lcap = h->lcap; kp.hcap = h->hcap; kp.hscap = h->hscap;
+  kp.lcap = site.lcap; kp.hcap = site.hcap; kp.hscap = site.hscap;
   kp.class_words = h->has_classes ? class_lds_words(h->n_classes) : 0;
   kp.all_policies = (h->has_classes || h->has_alpha || h->has_budget_modes || h->has_mc || h->time_c0 != 0) ? 1 : 0;
   kp.time_c0 = h->time_c0; kp.time_cp = h->time_cp; kp.time_cd = h->time_cd;
   if (h->time_c0 != 0) {  // the clock of a path stays below 2^30
-    const int64_t most_active = static_cast<int64_t>(h->lcap) + h->hcap;
+    const int64_t most_active = static_cast<int64_t>(site.lcap) + site.hcap;
     const int64_t d_max = h->time_c0 + static_cast<int64_t>(h->time_cp) * std::min<int64_t>(h->tau, h->M) +
                           static_cast<int64_t>(h->time_cd) * std::min<int64_t>(h->tau, most_active);
     if (n_steps * d_max >= kLimit) return FCS_EINVAL;
   }
-  kp.spill = reinterpret_cast<int32_t*>(static_cast<char*>(h->workspace) + h->blob_bytes_padded);
-  kp.spill_stride = h->spill_stride;
+  kp.spill = reinterpret_cast<int32_t*>(static_cast<char*>(site.workspace) + h->blob_bytes_padded);
+  kp.spill_stride = site.spill_stride;
   kp.trace_every = h->trace_every;
   kp.n_trace = h->trace_every > 0 ? static_cast<int32_t>(n_steps / h->trace_every) : 0;
   kp.hist_bins = h->hist_bins; kp.hist_shift = h->hist_shift; kp.max_requests = h->max_requests;
   kp.n_paths = static_cast<int32_t>(n_replicas * h->n_cells);
-  if (h->trace_every > 0 && (h->out.trace_q || h->out.trace_u) &&
-      static_cast<int64_t>(kp.n_paths) * kp.n_trace > h->out.trace_entries)
+  if (h->trace_every > 0 && (site.out.trace_q || site.out.trace_u) &&
+      static_cast<int64_t>(kp.n_paths) * kp.n_trace > site.out.trace_entries)
     return FCS_EINVAL;  // the caller's trace arrays are too short for this run
-  {
-    size_t need = 0;
-    if (fcs_workspace_bytes(h, h->bound_replicas, &need) != FCS_OK) return FCS_ESTATE;
-    kp.pace = reinterpret_cast<unsigned long long*>(static_cast<char*>(h->workspace) + need - 256);
-    kp.launch_seq = ++h->launch_seq;
-  }
-  kp.out = h->out;
+  kp.pace = site.pace;
+  kp.launch_seq = site.launch_seq;
+  kp.out = site.out;
   if (h->hist_bins == 0) kp.out.hist = nullptr;
   if (h->max_requests == 0) { kp.out.arrival_step = nullptr; kp.out.completion_step = nullptr; }
   if (h->trace_every == 0) { kp.out.trace_q = nullptr; kp.out.trace_u = nullptr; }
@@ -361,7 +394,68 @@ int fcs_run_from(fcs_handle h, int64_t replica_base, int64_t n_replicas, int64_t
   h->run_replicas = n_replicas;
   h->run_steps = n_steps;
   h->run_stream = stream;
+  h->run_out = site.out;
+  h->run_lcap = site.lcap;
+  h->run_hcap = site.hcap;
   return FCS_OK;
+}
+
+int fcs_run_from(fcs_handle h, int64_t replica_base, int64_t n_replicas, int64_t n_steps, uint64_t seed,
+                 void* stream) {
+  if (!h) return FCS_EINVAL;
+  if (!h->bound) return FCS_ESTATE;
+  if (n_replicas < 1 || n_replicas > h->bound_replicas) return FCS_EINVAL;
+  size_t need = 0;
+  if (fcs_workspace_bytes(h, h->bound_replicas, &need) != FCS_OK) return FCS_ESTATE;
+  LaunchSite site{};
+  site.workspace = h->workspace;
+  site.pace = reinterpret_cast<unsigned long long*>(static_cast<char*>(h->workspace) + need - 256);
+  site.launch_seq = ++h->launch_seq;
+  site.out = h->out;
+  site.lcap = h->lcap; site.hcap = h->hcap; site.hscap = h->hscap;
+  site.spill_stride = h->spill_stride;
+  return run_on(h, site, replica_base, n_replicas, n_steps, seed, stream);
+}
+
+int fcs_run_static(fcs_handle h, const fcs_outputs* o, int64_t n_replicas, int64_t n_steps, uint64_t seed,
+                   void* stream) {
+  if (!h || !o || !o->counters) return FCS_EINVAL;
+  LaunchSite site{};
+  int rc = geometry_for(h, n_replicas, &site.lcap, &site.hcap, &site.hscap);
+  if (rc != FCS_OK) return rc;
+  site.spill_stride = static_cast<int64_t>(kSpillWordsPerSlot) * site.hcap + static_cast<int64_t>(S_NFIELDS) * site.hscap;
+  // the same layout as a caller's workspace, the pacing words apart at the end of the array
+  const size_t spill_bytes = round_up(static_cast<size_t>(site.spill_stride) * sizeof(int32_t) *
+                                          static_cast<size_t>(n_replicas) * static_cast<size_t>(h->n_cells), 256);
+  if (h->blob_bytes_padded + spill_bytes > kStaticPaceOffset) return FCS_ENOMEM;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return FCS_EDEVICE;
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  StaticSite& st = g_static[dev];
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (st.ptr == nullptr) {  // set-up, once per device, with that device current
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return FCS_EDEVICE;
+    // the pacing words start at zero (a fill kernel, so that the call may be captured into a graph)
+    hipLaunchKernelGGL(fill_words_kernel, dim3(1), dim3(64), 0, s,
+                       reinterpret_cast<uint32_t*>(static_cast<char*>(p) + kStaticPaceOffset), 0u, 64);
+    if (hipGetLastError() != hipSuccess) return FCS_EDEVICE;
+    st.ptr = p;
+  }
+  if (st.blob_owner != h->uid) {  // another engine's tables (or none) lie there: upload this one's
+    st.blob_owner = 0;
+    if (hipMemcpyAsync(st.ptr, h->blob.data(), h->blob.size() * sizeof(uint32_t), hipMemcpyHostToDevice, s) !=
+        hipSuccess)
+      return FCS_EDEVICE;
+    // the blob is pageable host memory owned by the handle: wait so it may go away afterwards
+    if (hipStreamSynchronize(s) != hipSuccess) return FCS_EDEVICE;
+    st.blob_owner = h->uid;
+  }
+  site.workspace = st.ptr;
+  site.pace = reinterpret_cast<unsigned long long*>(static_cast<char*>(st.ptr) + kStaticPaceOffset);
+  site.launch_seq = ++st.launch_seq;
+  site.out = *o;
+  return run_on(h, site, 0, n_replicas, n_steps, seed, stream);
 }
 
 int fcs_run(fcs_handle h, int64_t n_replicas, int64_t n_steps, uint64_t seed, void* stream) {
@@ -385,7 +479,7 @@ int fcs_stats(fcs_handle h, int32_t cell, uint64_t* host_counters, fcs_summary* 
     }
     C = local.data();
   }
-  if (hipMemcpy(C, h->out.counters, sizeof(uint64_t) * n_paths * FCS_N_COUNTERS, hipMemcpyDeviceToHost) !=
+  if (hipMemcpy(C, h->run_out.counters, sizeof(uint64_t) * n_paths * FCS_N_COUNTERS, hipMemcpyDeviceToHost) !=
       hipSuccess)
     return FCS_EDEVICE;
   int64_t first_err = -1;
@@ -432,7 +526,7 @@ int fcs_stats(fcs_handle h, int32_t cell, uint64_t* host_counters, fcs_summary* 
 
 int fcs_percentile(fcs_handle h, int64_t num, int64_t den, int32_t* value, uint8_t* saturated) {
   if (!h || !value || den < 1 || num < 0 || num > den) return FCS_EINVAL;
-  if (!h->ran || h->hist_bins == 0 || !h->out.hist) return FCS_ESTATE;
+  if (!h->ran || h->hist_bins == 0 || !h->run_out.hist) return FCS_ESTATE;
   int rc = sync_last(h);
   if (rc != FCS_OK) return rc;
   const int64_t n_paths = h->run_replicas * h->n_cells;
@@ -446,7 +540,7 @@ int fcs_percentile(fcs_handle h, int64_t num, int64_t den, int32_t* value, uint8
   }
   for (int64_t p0 = 0; p0 < n_paths; p0 += batch) {
     const int64_t np = std::min(batch, n_paths - p0);
-    if (hipMemcpy(buf.data(), h->out.hist + p0 * bins, sizeof(uint32_t) * np * bins, hipMemcpyDeviceToHost) !=
+    if (hipMemcpy(buf.data(), h->run_out.hist + p0 * bins, sizeof(uint32_t) * np * bins, hipMemcpyDeviceToHost) !=
         hipSuccess)
       return FCS_EDEVICE;
     for (int64_t p = 0; p < np; ++p) {
@@ -496,10 +590,11 @@ int fcs_stability_bound(const fcs_params* p, double* lambda_star) {
 
 int fcs_geometry(fcs_handle h, int32_t* lds_slots, int32_t* lds_bytes, int32_t* spill_slots) {
   if (!h) return FCS_EINVAL;
-  if (!h->bound) return FCS_ESTATE;
-  if (lds_slots) *lds_slots = h->lcap;
-  if (lds_bytes) *lds_bytes = lds_words(h->lcap, h->has_classes ? class_lds_words(h->n_classes) : 0) * 4;
-  if (spill_slots) *spill_slots = h->hcap;
+  if (!h->bound && !h->ran) return FCS_ESTATE;
+  const int32_t lc = h->ran ? h->run_lcap : h->lcap, hc = h->ran ? h->run_hcap : h->hcap;
+  if (lds_slots) *lds_slots = lc;
+  if (lds_bytes) *lds_bytes = lds_words(lc, h->has_classes ? class_lds_words(h->n_classes) : 0) * 4;
+  if (spill_slots) *spill_slots = hc;
   return FCS_OK;
 }
 
