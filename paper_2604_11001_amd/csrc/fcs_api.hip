@@ -38,6 +38,7 @@ struct fcs_engine {
   bool has_mc = false;
   int32_t time_c0 = 0, time_cp = 0, time_cd = 0;
   int64_t classes_active = 0;  // CLASSES: most requests active at once when no prefill ever waits
+  double expected_active = 0.0;  // FLOW and GREEDY cells: estimate of the mean |P| of the busiest cell (below)
   size_t blob_bytes_padded = 0;
   // last run
   bool ran = false;
@@ -51,6 +52,8 @@ struct fcs_engine {
 namespace {
 
 constexpr int32_t kLimit = 1 << 30;
+// an expected active set up to this size gets one block of 256 LDS slots (see geometry_for)
+constexpr double kSmallActive = 180.0;
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -191,6 +194,51 @@ __global__ void fill_words_kernel(uint32_t* p, uint32_t v, int n) {
   if (i < n) p[i] = v;
 }
 
+// E[ceil(X / c)] of a threshold-table law
+double law_mean_chunks(const fcs_law& L, int64_t c) {
+  const double two32 = 4294967296.0;
+  double prev = 0.0, m = 0.0;
+  for (int32_t i = 0; i <= L.n_thr; ++i) {
+    const double cur = (i < L.n_thr) ? static_cast<double>(L.thr[i]) : two32;
+    const int64_t v = static_cast<int64_t>(L.lo) + i;
+    m += (cur - prev) / two32 * static_cast<double>((v + c - 1) / c);
+    prev = cur;
+  }
+  return m;
+}
+
+// Estimate of the time-average |P| of a FLOW or GREEDY cell, used only to size the LDS part of the active
+// set.  A request that is never held up is active for S = ceil(l / c) + o - 1 slots (Section 2.1 with
+// chunked prefill: the chunk that ends the prompt yields token 1), so by Little's law |P| is about
+// (activation rate) x E[S], the rate being at most the arrival rate and, under Algorithm 2, the mean
+// budget b.  The memory caps it: over its stay a request holds l per prefill slot and l + j in the
+// slot of token j, E[w] + E[l (ceil(l / c) - 1)] in all, so no more than M E[S] / that fit on average.
+double expected_active_of(const fcs_params* p, const fcs_cell& c) {
+  const double two32 = 4294967296.0;
+  const int64_t chunk = std::max<int64_t>(1, std::min<int64_t>(p->prefill_chunk, p->token_budget));
+  double es = 0.0, hold = 0.0, prev = 0.0;
+  for (int32_t k = 0; k < p->n_classes; ++k) {
+    const double cur = (k + 1 < p->n_classes) ? static_cast<double>(p->class_thr[k]) : two32;
+    const double pk = (cur - prev) / two32;
+    prev = cur;
+    double el, el2, eo, eo2;
+    law_moments(p->prompt[k], el, el2);
+    law_moments(p->decode[k], eo, eo2);
+    const double ech = law_mean_chunks(p->prompt[k], chunk);
+    es += pk * (ech + eo - 1.0);
+    // l and o independent; E[l (ceil(l / c) - 1)] taken as E[l] E[ceil(l / c) - 1], good enough for a size
+    hold += pk * (el * eo + 0.5 * (eo + eo2) + el * (ech - 1.0));
+  }
+  double lam, lam2;
+  law_moments(p->arrival[c.arrival], lam, lam2);
+  double rate = lam;
+  if (c.policy == FCS_POLICY_FLOW && c.budget_mode == FCS_BUDGET_SPLIT)
+    rate = std::min(rate, static_cast<double>(c.b_floor) + static_cast<double>(c.b_frac_thr) / two32);
+  const double by_rate = rate * es;
+  const double by_memory = hold > 0.0 ? static_cast<double>(p->capacity) * es / hold : by_rate;
+  return std::min(by_rate, by_memory);
+}
+
 int sync_last(fcs_engine* h) {
   return hipStreamSynchronize(static_cast<hipStream_t>(h->run_stream)) == hipSuccess ? FCS_OK : FCS_EDEVICE;
 }
@@ -262,6 +310,9 @@ int fcs_create(const fcs_params* p, fcs_handle* out) {
     std::memcpy(h->blob.data() + h->cells_off + 4 * i, &d, sizeof(d));
   }
   for (int32_t c = 0; c + 1 < p->n_classes; ++c) h->blob[h->class_off + c] = p->class_thr[c];
+  for (int32_t i = 0; i < p->n_cells; ++i)
+    if (p->cells[i].policy == FCS_POLICY_FLOW || p->cells[i].policy == FCS_POLICY_GREEDY)
+      h->expected_active = std::max(h->expected_active, expected_active_of(p, p->cells[i]));
   h->blob.insert(h->blob.end(), body.begin(), body.end());
   h->blob_bytes_padded = round_up(h->blob.size() * sizeof(uint32_t), 256);
   } catch (const std::bad_alloc&) {
@@ -280,11 +331,19 @@ static int geometry_for(fcs_engine* h, int64_t n_replicas, int32_t* lcap, int32_
   if (max_active == 0) max_active = std::min<int64_t>(std::max<int64_t>(h->M / (h->l_min + 1) + 1, h->classes_active), 8192);
   max_active = static_cast<int64_t>(round_up(static_cast<size_t>(max_active), kWave));
   int32_t lc = h->lds_slots_param;
+  const bool plain = !(h->has_classes || h->has_alpha || h->has_budget_modes || h->has_mc || h->time_c0 != 0);
+  if (lc == 0 && plain && n_paths > 2048 && h->expected_active <= kSmallActive) {
+    // The kernel of the FLOW and GREEDY cells runs four wavefronts per SIMD, and a path is a chain of
+    // dependent instructions: with more paths than the chip holds at two per SIMD, throughput is set by how
+    // many are resident.  One block of 256 slots (8.25 KB with the stack) lets 16 of them share a compute
+    // unit; it is taken when the expected active set leaves room for its fluctuations and for the dead
+    // slots between compactions.  A path whose active set outgrows it goes on in the spill region.
+    lc = kLdsBlock;
+  }
   if (lc == 0) {
     // spread the paths over the 256 compute units and give each wavefront an equal share of
-    // the 160 KB of LDS, between 4 and 8 wavefronts per unit (8 leaves 512 slots, which the
-    // hand-scheduled slot loop of the kernel needs; a path is a latency chain, so more resident
-    // wavefronts per unit buy less than running each of them in that loop)
+    // the 160 KB of LDS, between 4 and 8 wavefronts per unit (8 leaves 512 slots: both register blocks of
+    // the hand-scheduled slot loop)
     int64_t per_cu = (n_paths + 255) / 256;
     per_cu = std::min<int64_t>(std::max<int64_t>(per_cu, 4), 8);
     const int64_t words = (160 * 1024 / per_cu) / 4 - S_NFIELDS * kStackLds - kScratchWords -

@@ -39,6 +39,7 @@ constexpr int kLdsBlock = 256;       // slots per b128 pass over the LDS tier
 constexpr int kStackLds = 64;        // evicted-stack entries kept in LDS
 constexpr int kScratchWords = 64;
 constexpr int kCompactSlack = 64;    // compact when this many dead slots have accumulated
+constexpr int kLdsCompactMin = 16;   // ... or this many when the next slot would be the first outside LDS
 constexpr int kMaxCountThr = 63;
 constexpr int kMaxClasses = 16;
 

@@ -141,17 +141,24 @@ __device__ __forceinline__ void st4(int32_t* p, v4i v) {
 enum { SL_SUM_U = 0, SL_SUM_P, SL_SUM_Q, SL_DEC_TOK, SL_ACT, SL_DONE, SL_EVICT, SL_OVF, SL_PF_TOK,
        SL_STALLED, SL_COUNT };
 
+// The kernel of the FLOW and GREEDY cells is held to 128 vector registers, so that four wavefronts fit a
+// SIMD (the fixed registers of the assembly loop are v84-v127): with 256 LDS slots per path a compute unit
+// then holds 16 paths, which is what hides the latencies of a path's instruction chain best.
 #define FCS_ALL_POLICIES 0
 #define FCS_KERNEL fcs_sim_kernel
+#define FCS_KERNEL_ATTR __attribute__((amdgpu_waves_per_eu(4, 4)))
 #include "fcs_sim_kernel.inc"
 #undef FCS_ALL_POLICIES
 #undef FCS_KERNEL
+#undef FCS_KERNEL_ATTR
 
 #define FCS_ALL_POLICIES 1
 #define FCS_KERNEL fcs_sim_all_kernel
+#define FCS_KERNEL_ATTR
 #include "fcs_sim_kernel.inc"
 #undef FCS_ALL_POLICIES
 #undef FCS_KERNEL
+#undef FCS_KERNEL_ATTR
 
 }  // namespace
 
