@@ -11,6 +11,8 @@ Prints ONE JSON line:
   and one write of a per-request token counter) next to what the kernel really moves and to the bound that
   does hold for it, the issue rate of the scalar instruction stream of a path (``roofline.issue``);
 * ``all_configs``: the same figures for the other four benchmark configurations, one pass each;
+* ``event_skipping``: the tiny configuration and the timed one again with runs of uneventful slots advanced
+  in one go (same outputs; reported apart because it changes what a "step" costs);
 * ``cpu_baseline``: the CPU oracle timed on a bounded sample of the same workload on the host cores.
 """
 from __future__ import annotations
@@ -294,6 +296,18 @@ def main() -> int:
                          "clocks_per_slot_and_simd": r["clocks_per_slot_and_simd"],
                          "lds_slots": r["geo"]["lds_slots"]})
         line["all_configs"] = rows
+        # event skipping (runs of uneventful slots advanced in one go): same outputs, another accounting of
+        # the time, so it is reported apart from the step-synchronous figures above
+        skips = []
+        for ci in (0, args.config):
+            w = build(fcs.stability_bound, ci)
+            r = measure(w, 2, 1, skip_idle=True)
+            base = rows[ci]
+            assert r["request_steps"] == base["request_steps"]
+            skips.append({"config": ci, "workload": w.name, "kernel_ms": r["kernel_ms"],
+                          "kernel_ms_step_synchronous": base["kernel_ms"],
+                          "request_steps_per_s": r["request_steps"] / (r["kernel_ms"] * 1e-3)})
+        line["event_skipping"] = skips
     if not args.no_cpu_baseline:
         import oracle
         line["cpu_baseline"] = cpu_baseline(build(oracle.stability_bound))

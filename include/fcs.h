@@ -135,9 +135,10 @@ typedef struct fcs_params {
   int32_t hist_bins;      /* > 0: latency histogram, bucket = min(lat >> shift, bins-1) */
   int32_t hist_shift;
   int32_t max_requests;   /* > 0: per-path length of arrival_step/completion_step  */
-  int32_t max_active;     /* per-path capacity of the active set; 0 = default:
+  int32_t max_active;     /* per-path capacity of the active set, up to 2^24; 0 = default:
                            * M / (min l + 1) + 1, and with CLASSES cells at least
-                           * sum_k b_k (ceil(l_k / min(c, tau)) + o_k + 1); at most 8192 */
+                           * sum_k b_k (ceil(l_k / min(c, tau)) + o_k + 1); the default
+                           * is at most 8192 */
   int32_t lds_slots;      /* active-set slots kept in LDS per path; 0 = automatic  */
   /* Slots of variable duration (all three 0: every slot lasts one time unit).  Time runs
    * in the units of the arrival laws: n_u requests arrive in unit u; slot t starts at time
@@ -148,7 +149,19 @@ typedef struct fcs_params {
    * the n_steps slots took.  time_c0 >= 1; not with CLASSES cells; n_steps times the
    * longest possible d_t must stay below 2^30 (checked by fcs_run). */
   int32_t time_c0, time_cp, time_cd;
+  /* FCS_FLAG_* bits, 0 = none.
+   * FCS_FLAG_SKIP_IDLE: event skipping.  A run of slots in which nothing happens but decode growth
+   * (no arrival, no admission, no prefill, no completion, no overflow, no trace sample) is advanced in one
+   * go inside the kernel's slot loop: with n decoding requests and usage U before the run, k such slots
+   * add k U + n k (k + 1) / 2 to sum_t U_t (the growth term of the expression for U_t in the proof of
+   * Theorem 2, summed), k |P| and k |Q| to the other sums, and leave U + k n.  Every output is the same as
+   * without the flag; only the time differs.  Engines whose cells are all FLOW or GREEDY, no time model.
+   * FCS_FLAG_GENERAL_CODE: a test switch; every slot runs in the kernel's general code and none in the
+   * hand-scheduled loop (the two are separate renditions of the same slot and must agree). */
+  int32_t flags;
 } fcs_params;
+
+enum { FCS_FLAG_SKIP_IDLE = 1, FCS_FLAG_GENERAL_CODE = 2 };
 
 /* Per-path counters, uint64 each, FCS_N_COUNTERS per path. */
 enum {
@@ -199,10 +212,12 @@ typedef struct fcs_outputs {
   int64_t trace_entries;     /* int32 entries that trace_q and trace_u each hold    */
 } fcs_outputs;
 /* path = cell * n_replicas + replica, n_paths = n_cells * n_replicas, with the
- * n_replicas of fcs_bind for counters, hist, arrival_step and completion_step
- * (a run of fewer replicas uses the leading rows).  The trace rows are packed
- * by the run: n_replicas and n_steps are those of fcs_run, which refuses a run
- * whose n_paths * (n_steps / trace_every) exceeds trace_entries. */
+ * n_replicas of the RUN for every array: a run of fewer replicas than were bound
+ * packs its rows at the start of the arrays (cell c begins at row c * n_replicas
+ * of that run), and fcs_stats / fcs_percentile index the same way.  The arrays
+ * must hold the rows of the largest run; the trace rows also depend on n_steps,
+ * and fcs_run refuses a run whose n_paths * (n_steps / trace_every) exceeds
+ * trace_entries. */
 
 typedef struct fcs_summary {
   int64_t n_paths;

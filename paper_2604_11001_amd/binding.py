@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libfcs.so")
 
 FCS_OK, FCS_EINVAL, FCS_ENOMEM, FCS_ESTATE, FCS_EOVERFLOW, FCS_EDEVICE = 0, -1, -2, -3, -4, -5
 POLICY_FLOW, POLICY_GREEDY = 0, 1
+FLAG_SKIP_IDLE, FLAG_GENERAL_CODE = 1, 2
 
 
 class FcsError(RuntimeError):
@@ -49,6 +50,7 @@ class fcs_params(C.Structure):
         ("trace_every", C.c_int32), ("hist_bins", C.c_int32), ("hist_shift", C.c_int32),
         ("max_requests", C.c_int32), ("max_active", C.c_int32), ("lds_slots", C.c_int32),
         ("time_c0", C.c_int32), ("time_cp", C.c_int32), ("time_cd", C.c_int32),
+        ("flags", C.c_int32),
     ]
 
 
@@ -127,7 +129,7 @@ def _law(law, keep):
     return fcs_law(int(law.lo), int(thr.size), thr.ctypes.data_as(C.POINTER(C.c_uint32)))
 
 
-def make_params(wl, max_active: int = 0, lds_slots: int = 0):
+def make_params(wl, max_active: int = 0, lds_slots: int = 0, flags: int = 0):
     """Marshals a workload description into fcs_params; returns (params, keep-alive list)."""
     keep = []
     mix = wl.mixture
@@ -167,6 +169,7 @@ def make_params(wl, max_active: int = 0, lds_slots: int = 0):
     p.trace_every, p.hist_bins, p.hist_shift = int(wl.trace_every), int(wl.hist_bins), int(wl.hist_shift)
     p.max_requests, p.max_active, p.lds_slots = int(wl.max_requests), int(max_active), int(lds_slots)
     p.time_c0, p.time_cp, p.time_cd = (int(v) for v in getattr(wl, "time_model", (0, 0, 0)))
+    p.flags = int(flags)
     return p, keep
 
 
@@ -186,7 +189,7 @@ class Engine:
     """Owns one fcs handle plus the torch device buffers bound to it."""
 
     def __init__(self, wl, n_replicas=None, n_steps=None, device="cuda:0", max_active=0, lds_slots=0,
-                 static_workspace=False):
+                 static_workspace=False, skip_idle=False, general_code=False):
         """static_workspace: no workspace is allocated or bound; ``run`` goes through fcs_run_static, on
         the device memory that the library itself holds."""
         import torch
@@ -199,8 +202,10 @@ class Engine:
         self.n_steps = int(wl.n_steps if n_steps is None else n_steps)
         self.n_cells = len(wl.cells)
         self.n_paths = self.n_cells * self.n_replicas
+        self.bound_replicas = self.n_replicas
         self._h = C.c_void_p()
-        params, keep = make_params(wl, max_active, lds_slots)
+        params, keep = make_params(wl, max_active, lds_slots,
+                                   (FLAG_SKIP_IDLE if skip_idle else 0) | (FLAG_GENERAL_CODE if general_code else 0))
         _check(lib().fcs_create(C.byref(params), C.byref(self._h)), "fcs_create")
         del keep
         nbytes = C.c_size_t(0)
@@ -238,9 +243,15 @@ class Engine:
         _check(lib().fcs_geometry(self._h, C.byref(a), C.byref(b), C.byref(c)), "fcs_geometry")
         return {"lds_slots": a.value, "lds_bytes": b.value, "spill_slots": c.value}
 
-    def run(self, seed=None, n_steps=None, replica_base=0, stream=None):
-        """fcs_run_from on the current torch stream (asynchronous)."""
+    def run(self, seed=None, n_steps=None, replica_base=0, stream=None, n_replicas=None):
+        """fcs_run_from on the current torch stream (asynchronous).  n_replicas: fewer replicas per cell than
+        the engine was created for; the rows of every output array are then packed by that number."""
         torch = self.torch
+        if n_replicas is not None:
+            if not 1 <= int(n_replicas) <= self.bound_replicas:
+                raise ValueError("n_replicas beyond what the engine was created for")
+            self.n_replicas = int(n_replicas)
+            self.n_paths = self.n_cells * self.n_replicas
         if stream is None:
             stream = torch.cuda.current_stream(self.device).cuda_stream
         seed = int(self.wl.seed if seed is None else seed)

@@ -16,6 +16,7 @@ SOURCES = ["fcs_api.hip", "fcs_sim.hip"]
 # kernel of the FLOW and GREEDY cells), and no scratch memory (state that leaves the registers would put
 # memory round trips on a path's instruction chain).
 RESOURCE_LIMITS = {"fcs_sim_kernel": {"VGPRs": 128, "ScratchSize [bytes/lane]": 0},
+                   "fcs_sim_skip_kernel": {"VGPRs": 128, "ScratchSize [bytes/lane]": 0},
                    "fcs_sim_all_kernel": {"VGPRs": 256, "ScratchSize [bytes/lane]": 0}}
 
 

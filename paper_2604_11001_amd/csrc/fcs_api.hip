@@ -37,6 +37,7 @@ struct fcs_engine {
   bool has_budget_modes = false;  // FLOW cells whose B_t is not the Bernoulli split
   bool has_mc = false;
   int32_t time_c0 = 0, time_cp = 0, time_cd = 0;
+  int32_t flags = 0;
   int64_t classes_active = 0;  // CLASSES: most requests active at once when no prefill ever waits
   double expected_active = 0.0;  // FLOW and GREEDY cells: estimate of the mean |P| of the busiest cell (below)
   size_t blob_bytes_padded = 0;
@@ -125,6 +126,12 @@ bool params_ok(const fcs_params* p) {
     if (p->time_c0 < 1 || p->time_cp > (1 << 15) || p->time_cd > (1 << 15) || p->time_c0 > (1 << 20)) return false;
     for (int32_t i = 0; i < p->n_cells; ++i)
       if (p->cells[i].policy == FCS_POLICY_CLASSES) return false;
+  }
+  if (p->flags & ~(FCS_FLAG_SKIP_IDLE | FCS_FLAG_GENERAL_CODE)) return false;
+  if (p->flags & FCS_FLAG_SKIP_IDLE) {  // only the kernel of the FLOW and GREEDY cells has it
+    if (p->time_c0 != 0) return false;
+    for (int32_t i = 0; i < p->n_cells; ++i)
+      if (p->cells[i].policy > FCS_POLICY_GREEDY || p->cells[i].budget_mode != FCS_BUDGET_SPLIT) return false;
   }
   if (p->trace_every < 0 || p->hist_bins < 0 || p->hist_bins > (1 << 24)) return false;
   if (p->hist_shift < 0 || p->hist_shift > 30 || p->max_requests < 0) return false;
@@ -260,6 +267,7 @@ int fcs_create(const fcs_params* p, fcs_handle* out) {
   h->trace_every = p->trace_every; h->hist_bins = p->hist_bins; h->hist_shift = p->hist_shift;
   h->max_requests = p->max_requests; h->max_active = p->max_active; h->lds_slots_param = p->lds_slots;
   h->time_c0 = p->time_c0; h->time_cp = p->time_cp; h->time_cd = p->time_cd;
+  h->flags = p->flags;
   h->l_min = p->prompt[0].lo;
   for (int32_t c = 1; c < p->n_classes; ++c) h->l_min = std::min(h->l_min, p->prompt[c].lo);
 
@@ -426,6 +434,7 @@ static int run_on(fcs_engine* h, const LaunchSite& site, int64_t replica_base, i
   kp.class_words = h->has_classes ? class_lds_words(h->n_classes) : 0;
   kp.all_policies = (h->has_classes || h->has_alpha || h->has_budget_modes || h->has_mc || h->time_c0 != 0) ? 1 : 0;
   kp.time_c0 = h->time_c0; kp.time_cp = h->time_cp; kp.time_cd = h->time_cd;
+  kp.flags = h->flags;
   if (h->time_c0 != 0) {  // the clock of a path stays below 2^30
     const int64_t most_active = static_cast<int64_t>(site.lcap) + site.hcap;
     const int64_t d_max = h->time_c0 + static_cast<int64_t>(h->time_cp) * std::min<int64_t>(h->tau, h->M) +

@@ -56,6 +56,7 @@ struct KParams {
   int32_t class_words;        // LDS words of the per-class tables (0 without CLASSES cells)
   int32_t all_policies;       // some cell is neither FLOW nor GREEDY: run the kernel built with all policies
   int32_t time_c0, time_cp, time_cd;  // slots of variable duration (all-policies kernel), else 0
+  int32_t flags;              // FCS_FLAG_*
   int32_t* spill;             // per path: kSpillWordsPerSlot*hcap + S_NFIELDS*hscap words
   int64_t spill_stride;       // words per path
   int32_t trace_every, n_trace, hist_bins, hist_shift, max_requests;

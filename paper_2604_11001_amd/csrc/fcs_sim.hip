@@ -145,26 +145,38 @@ enum { SL_SUM_U = 0, SL_SUM_P, SL_SUM_Q, SL_DEC_TOK, SL_ACT, SL_DONE, SL_EVICT, 
 // SIMD (the fixed registers of the assembly loop are v84-v127): with 256 LDS slots per path a compute unit
 // then holds 16 paths, which is what hides the latencies of a path's instruction chain best.
 #define FCS_ALL_POLICIES 0
+#define FCS_SKIP_IDLE 0
 #define FCS_KERNEL fcs_sim_kernel
 #define FCS_KERNEL_ATTR __attribute__((amdgpu_waves_per_eu(4, 4)))
+#include "fcs_sim_kernel.inc"
+#undef FCS_KERNEL
+#undef FCS_SKIP_IDLE
+
+// the same with event skipping in the slot loop (FCS_FLAG_SKIP_IDLE)
+#define FCS_SKIP_IDLE 1
+#define FCS_KERNEL fcs_sim_skip_kernel
 #include "fcs_sim_kernel.inc"
 #undef FCS_ALL_POLICIES
 #undef FCS_KERNEL
 #undef FCS_KERNEL_ATTR
+#undef FCS_SKIP_IDLE
 
 #define FCS_ALL_POLICIES 1
+#define FCS_SKIP_IDLE 0
 #define FCS_KERNEL fcs_sim_all_kernel
 #define FCS_KERNEL_ATTR
 #include "fcs_sim_kernel.inc"
 #undef FCS_ALL_POLICIES
 #undef FCS_KERNEL
 #undef FCS_KERNEL_ATTR
+#undef FCS_SKIP_IDLE
 
 }  // namespace
 
 int launch_sim(const KParams& kp, void* stream) {
   const size_t lds = static_cast<size_t>(lds_words(kp.lcap, kp.class_words)) * sizeof(int32_t);
-  void (*kernel)(const KParams) = kp.all_policies ? fcs_sim_all_kernel : fcs_sim_kernel;
+  void (*kernel)(const KParams) = kp.all_policies ? fcs_sim_all_kernel
+                                  : (kp.flags & FCS_FLAG_SKIP_IDLE) ? fcs_sim_skip_kernel : fcs_sim_kernel;
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));

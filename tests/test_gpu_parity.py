@@ -565,3 +565,88 @@ def test_repeated_launches_are_identical():
     for k in runs[0]:
         assert np.array_equal(runs[0][k], runs[1][k]) and np.array_equal(runs[0][k], runs[2][k]), k
     compare(eng, wl, label="third launch")
+
+
+# ---- event skipping, and the general code alone -----------------------------------------------------------------
+
+def _plain_random_workload(rng, k):
+    """FLOW and GREEDY cells only (what the loop with event skipping serves), from idle to overloaded."""
+    l_hi = int(rng.integers(2, 60))
+    prompt = laws.uniform_int(int(rng.integers(1, l_hi)), l_hi)
+    o_cap = int(rng.integers(1, 150))
+    decode = laws.point(o_cap) if rng.random() < 0.2 else laws.geometric(float(rng.uniform(1.0, 40.0)), cap=o_cap)
+    M = int(l_hi + o_cap + rng.integers(0, 4000))
+    lam = float(rng.choice([0.01, 0.03, 0.1, 0.3, 1.0, 2.0]))
+    tau = INF if rng.random() < 0.3 else int(rng.integers(8, 300))
+    chunk = INF if rng.random() < 0.3 else int(rng.integers(2, 64))
+    cells = (flow_cell(0, float(rng.uniform(0.02, 2.0))), greedy_cell(0), flow_cell(0, lam * 1.05))
+    return Workload(name=f"plain-{k}", capacity=M, token_budget=tau, prefill_chunk=chunk,
+                    mixture=laws.single(prompt, decode), arrival_laws=(laws.poisson_counts(lam),), cells=cells,
+                    n_replicas=3, n_steps=int(rng.integers(60, 1500)), seed=3000 + k,
+                    trace_every=int(rng.choice([0, 7, 64, 100])), hist_bins=64, hist_shift=int(rng.integers(0, 3)),
+                    max_requests=4096)
+
+
+def test_event_skipping_changes_no_output():
+    # configuration 0: seven slots in eight have no arrival, admission, prefill or completion
+    wl = configs.config0(oracle.stability_bound)
+    eng = run(wl, skip_idle=True)
+    got, _, _ = compare(eng, wl, label="cfg0 with event skipping")
+    check_summary(eng, wl, got)
+    # long idle stretches that end at a window border, a trace sample, the horizon; no arrivals at all
+    quiet = configs.toy(n_replicas=4, n_steps=1000, lam=0.02, b=0.5, trace_every=37)
+    compare(run(quiet, skip_idle=True), quiet, label="quiet")
+    for T in (1, 2, 63, 64, 65, 130):
+        w = quiet.scaled(n_steps=T)
+        compare(run(w, skip_idle=True), w, label=f"quiet T={T}")
+    none = quiet.scaled(arrival_laws=(laws.poisson_counts(0.0),))
+    compare(run(none, skip_idle=True), none, label="no arrivals")
+    # a full memory with rare arrivals: usage grows towards M during the idle stretches (the overflow test
+    # inside a run of skipped slots) and evictions follow
+    tight = configs.toy(capacity=400, token_budget=512, prefill_chunk=512, lam=0.08, b=2.0, l_range=(4, 40),
+                        o_mean=60.0, o_cap=300, n_replicas=8, n_steps=4000)
+    got, _, _ = compare(run(tight, skip_idle=True), tight, label="tight")
+    assert got["evictions"].sum() > 0
+    # eviction- and stall-heavy cases, where hardly anything can be skipped
+    for w in (configs.toy(), configs.toy(capacity=300, token_budget=40, prefill_chunk=8, lam=0.9, b=1.5, seed=12)):
+        compare(run(w, skip_idle=True), w, label="toy with event skipping")
+    rng = np.random.default_rng(20261128)
+    for k in range(60):
+        w = _plain_random_workload(rng, k)
+        kw = dict(lds_slots=256, max_active=4096) if k % 4 == 0 else {}
+        compare(run(w, skip_idle=True, **kw), w, label=f"{w.name} M={w.capacity} tau={w.token_budget} T={w.n_steps}")
+    # refused where the kernel with event skipping does not apply
+    with pytest.raises(fcs.FcsError):
+        fcs.Engine(configs.alpha_sweep(n_replicas=2, n_steps=10), skip_idle=True)
+
+
+def test_general_code_and_hand_scheduled_loop_agree():
+    # the two renditions of a slot, forced apart: every slot in the general code against the default
+    rng = np.random.default_rng(20261129)
+    cases = [configs.toy(), configs.toy(capacity=300, token_budget=40, prefill_chunk=8, lam=0.9, b=1.5, seed=12),
+             configs.config1(oracle.stability_bound).scaled(n_replicas=4, n_steps=6000, max_requests=1 << 14)]
+    cases += [_plain_random_workload(rng, k) for k in range(40)]
+    for w in cases:
+        a, b = run(w), run(w, general_code=True)
+        ga, _ = a.stats()
+        gb, _ = b.stats()
+        for k in ga:
+            assert np.array_equal(ga[k], gb[k]), (w.name, k)
+        for name in ("trace_q", "trace_u", "hist", "arrival_step", "completion_step"):
+            ta, tb = getattr(a, name), getattr(b, name)
+            if ta is not None:
+                assert np.array_equal(ta.cpu().numpy(), tb.cpu().numpy()), (w.name, name)
+    compare(run(cases[2], general_code=True), cases[2], replica_ids=[0, 3], label="cfg1 scaled, general code")
+
+
+def test_a_run_of_fewer_replicas_than_were_bound():
+    # rows are packed by the run: path = cell * (replicas of the run) + replica
+    wl = configs.toy(n_replicas=8, n_steps=500)
+    eng = fcs.Engine(wl)                 # bound for 8 replicas per cell
+    eng.run(n_replicas=3)
+    small = wl.scaled(n_replicas=3)
+    got, _, _ = compare(eng, small, check_requests=False, label="3 of 8 replicas")
+    comp = eng.completion_step.cpu().numpy()[: eng.n_paths]
+    for ci in range(len(wl.cells)):
+        ref = oracle.run_cell(small, ci)
+        assert np.array_equal(ref["completion_step"], comp[ci * 3:(ci + 1) * 3]), ci
