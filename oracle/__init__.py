@@ -268,3 +268,86 @@ def percentile_from_hist(hist, num, den, shift=0):
     cum = np.cumsum(hist)
     b = int(np.searchsorted(cum, k, side="left"))
     return b << shift, b == hist.size - 1
+
+
+# ---- the oracle under the host compiler's sanitizers ------------------------------------------------
+
+def case_tokens(wl, cell_index, replica_ids, n_steps=None, forced=None, forced_B=None):
+    """One case as the flat list of integers that replay_main.cpp reads (the fields of fo_config in order)."""
+    cell = wl.cells[cell_index]
+    mix = wl.mixture
+    nc = len(mix.classes)
+
+    def law(L):
+        thr = [int(v) for v in np.asarray(L.thr, dtype=np.uint32)]
+        return [int(L.lo), len(thr)] + thr
+
+    t = [int(cell.policy), nc, int(wl.capacity), int(wl.token_budget), int(wl.prefill_chunk), int(cell.b_floor),
+         int(cell.b_frac_thr)]
+    t += law(wl.arrival_laws[cell.arrival])
+    t += [int(v) for v in np.asarray(mix.class_thr, dtype=np.uint32)][: max(nc - 1, 0)]
+    for c in mix.classes:
+        t += law(c.prompt)
+    for c in mix.classes:
+        t += law(c.decode)
+    t += [int(wl.trace_every), int(wl.hist_bins), int(wl.hist_shift), int(wl.max_requests)]
+    if forced is None:
+        t += [-1]
+    else:
+        cols = [list(map(int, a)) for a in forced]
+        n = len(cols[0])
+        if cell.policy == 2:  # (slot, class)
+            cols = [cols[0], [0] * n, [0] * n, cols[1]]
+        else:                 # (slot, l, o)
+            cols = cols + [[0] * n]
+        t += [n] + cols[0] + cols[1] + cols[2] + cols[3]
+    fb = [] if forced_B is None else [int(v) for v in forced_B]
+    t += [len(fb)] + fb
+    if cell.policy == 2:
+        t += [1]
+        for a in cell.class_arrival:
+            t += law(wl.arrival_laws[a])
+        t += [int(b) for b in cell.class_budget]
+    else:
+        t += [0]
+    t += [protect_limit(cell.alpha, wl.capacity) if cell.policy == 3 else 0]
+    if cell.budget_law >= 0:
+        t += [1] + law(wl.arrival_laws[cell.budget_law]) + [0]
+    elif cell.credit_b16 > 0:
+        t += [2, 0, 0, int(cell.credit_b16)]
+    else:
+        t += [0, 0, 0, 0]
+    t += [int(cell.assumed_o) if cell.policy == 4 else 0]
+    t += [int(v) for v in getattr(wl, "time_model", (0, 0, 0))]
+    ids = [int(v) for v in replica_ids]
+    t += [len(ids)] + ids + [int(wl.n_steps if n_steps is None else n_steps), int(wl.seed)]
+    return t
+
+
+def build_sanitized(out_dir) -> str:
+    """replay_main.cpp with the address and undefined-behaviour sanitizers of the host compiler."""
+    exe = os.path.join(out_dir, "fcs_oracle_replay_asan")
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+           "-fno-omit-frame-pointer", "-pthread", "-o", exe, os.path.join(_HERE, "replay_main.cpp")]
+    subprocess.run(cmd, check=True)
+    return exe
+
+
+def replay(exe, tokens):
+    """Runs the driver on one case; returns a list of (counters dict, completion slots, histogram) per replica."""
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([exe], input=" ".join(map(str, tokens)), capture_output=True, text=True, env=env)
+    if r.returncode != 0:
+        raise RuntimeError(f"sanitized oracle failed (rc={r.returncode}):\n{r.stderr[-4000:]}")
+    names = counter_names()
+    rows, cur = [], None
+    for ln in r.stdout.splitlines():
+        kind, *vals = ln.split()
+        if kind == "counters":
+            cur = [dict(zip(names, map(int, vals))), None, None]
+            rows.append(cur)
+        elif kind == "completion":
+            cur[1] = np.array(list(map(int, vals)), dtype=np.int32)
+        elif kind == "hist":
+            cur[2] = np.array(list(map(int, vals)), dtype=np.uint32)
+    return rows
