@@ -20,7 +20,7 @@
  *      arrival stream n_{t,k}, its own FIFO queue and an integer budget b_k; in
  *      class order the first min(b_k, |Q_k|) requests of class k join P.
  *      ALPHA (alpha-protection greedy baseline, Section 4.1): as GREEDY, against
- *      protect_limit = (1 - alpha) M instead of M.
+ *      floor((1 - alpha) M) instead of M (fcs_protect_limit).
  *      MC (memory-check benchmark, Section 4.1): first come first served, the
  *      head joins P only if the memory stays within M in every future slot of the
  *      prediction in which each request produces assumed_o tokens, one per slot
@@ -104,7 +104,8 @@ typedef struct fcs_cell {
   const int32_t* class_arrival; /* CLASSES: n_classes indices into fcs_params.arrival, */
                                 /*   the law of n_{t,k} of each class (host pointer)   */
   const int32_t* class_budget;  /* CLASSES: n_classes budgets b_k, 0 .. 64, sum <= 64  */
-  int32_t protect_limit;        /* ALPHA: (1 - alpha) M rounded down, 0 .. M           */
+  double alpha;                 /* ALPHA: protected share of the memory, 0 <= alpha <= 1;   */
+                                /*   admission may fill fcs_protect_limit(alpha, M) tokens  */
   int32_t budget_mode;          /* FLOW: how B_t is formed.  FCS_BUDGET_SPLIT (0): b_floor  */
                                 /*   + [u < b_frac_thr]; FCS_BUDGET_LAW: drawn from the     */
                                 /*   count law fcs_params.arrival[budget_law] (any bounded  */
@@ -298,6 +299,11 @@ int fcs_percentile(fcs_handle h, int64_t num, int64_t den, int32_t* value, uint8
 /* lambda* = M / E[l o + (o + o^2)/2] for the parameter's mixture (Proposition 2,
  * eq. 3), l and o independent within a class.  Host only. */
 int fcs_stability_bound(const fcs_params* params, double* lambda_star);
+
+/* What admission may fill under the alpha-protection greedy baseline of Section 4.1:
+ * *limit = floor((1 - alpha) * capacity), the product formed in IEEE double precision.
+ * FCS_EINVAL unless 0 <= alpha <= 1 and 1 <= capacity <= 2^30.  Host only. */
+int fcs_protect_limit(double alpha, int32_t capacity, int32_t* limit);
 
 /* Launch geometry of the last run, or before any run the one chosen by fcs_bind: LDS slots per path,
  * LDS bytes per workgroup, spill slots per path. */

@@ -4,4 +4,4 @@ The product is ``libfcs.so`` (hand-written HIP for gfx950 behind the C ABI of
 ``include/fcs.h``); this package is its thin ctypes binding.
 """
 from .binding import (Engine, FcsError, POLICY_FLOW, POLICY_GREEDY, counter_names, lib,  # noqa: F401
-                      stability_bound, strerror)
+                      protect_limit, stability_bound, strerror)

@@ -9,7 +9,6 @@ without a GPU (so the exported symbols can be checked), but creating an
 from __future__ import annotations
 
 import ctypes as C
-import math
 import os
 
 import numpy as np
@@ -36,7 +35,7 @@ class fcs_cell(C.Structure):
     _fields_ = [("policy", C.c_int32), ("arrival", C.c_int32), ("b_floor", C.c_int32),
                 ("b_frac_thr", C.c_uint32),
                 ("class_arrival", C.POINTER(C.c_int32)), ("class_budget", C.POINTER(C.c_int32)),
-                ("protect_limit", C.c_int32), ("budget_mode", C.c_int32), ("budget_law", C.c_int32),
+                ("alpha", C.c_double), ("budget_mode", C.c_int32), ("budget_law", C.c_int32),
                 ("budget_b16", C.c_uint32), ("assumed_o", C.c_int32)]
 
 
@@ -75,7 +74,7 @@ class fcs_summary(C.Structure):
 
 
 EXPORTS = ["fcs_create", "fcs_workspace_bytes", "fcs_bind", "fcs_run", "fcs_run_from", "fcs_run_static", "fcs_stats",
-           "fcs_percentile", "fcs_stability_bound", "fcs_geometry", "fcs_destroy", "fcs_strerror",
+           "fcs_percentile", "fcs_stability_bound", "fcs_protect_limit", "fcs_geometry", "fcs_destroy", "fcs_strerror",
            "fcs_n_counters", "fcs_counter_name"]
 
 _lib = None
@@ -98,6 +97,7 @@ def lib():
         L.fcs_stats.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(fcs_summary)]
         L.fcs_percentile.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]
         L.fcs_stability_bound.argtypes = [C.POINTER(fcs_params), C.POINTER(C.c_double)]
+        L.fcs_protect_limit.argtypes = [C.c_double, C.c_int32, C.POINTER(C.c_int32)]
         L.fcs_geometry.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.fcs_destroy.argtypes = [C.c_void_p]
         L.fcs_destroy.restype = None
@@ -150,8 +150,8 @@ def make_params(wl, max_active: int = 0, lds_slots: int = 0, flags: int = 0):
             cells[i].budget_mode, cells[i].budget_b16 = 2, int(c.credit_b16)
         if int(c.policy) == 4:  # memory-check benchmark
             cells[i].assumed_o = int(c.assumed_o)
-        if int(c.policy) == 3:  # alpha-protection greedy: admission may fill (1 - alpha) M, rounded down
-            cells[i].protect_limit = int(math.floor((1.0 - float(c.alpha)) * int(wl.capacity)))
+        if int(c.policy) == 3:  # alpha-protection greedy: the protected share of the memory
+            cells[i].alpha = float(c.alpha)
         if getattr(c, "class_arrival", ()):  # per-class arrival laws and budgets (Algorithm 1)
             ca = np.ascontiguousarray(c.class_arrival, dtype=np.int32)
             cb = np.ascontiguousarray(c.class_budget, dtype=np.int32)
@@ -171,6 +171,13 @@ def make_params(wl, max_active: int = 0, lds_slots: int = 0, flags: int = 0):
     p.time_c0, p.time_cp, p.time_cd = (int(v) for v in getattr(wl, "time_model", (0, 0, 0)))
     p.flags = int(flags)
     return p, keep
+
+
+def protect_limit(alpha, capacity) -> int:
+    """fcs_protect_limit (host only, no GPU needed)."""
+    out = C.c_int32(0)
+    _check(lib().fcs_protect_limit(float(alpha), int(capacity), C.byref(out)), "fcs_protect_limit")
+    return int(out.value)
 
 
 def stability_bound(mixture, capacity) -> float:

@@ -97,7 +97,7 @@ bool params_ok(const fcs_params* p) {
       const int64_t most_active = p->max_active > 0 ? p->max_active : 8192;
       if ((l_max + 2 * static_cast<int64_t>(c.assumed_o)) * most_active >= (1ll << 31)) return false;
     }
-    if (c.policy == FCS_POLICY_ALPHA && (c.protect_limit < 0 || c.protect_limit > p->capacity)) return false;
+    if (c.policy == FCS_POLICY_ALPHA && !(c.alpha >= 0.0 && c.alpha <= 1.0)) return false;
     if (c.budget_mode < FCS_BUDGET_SPLIT || c.budget_mode > FCS_BUDGET_CREDIT) return false;
     if (c.budget_mode != FCS_BUDGET_SPLIT && c.policy != FCS_POLICY_FLOW) return false;
     if (c.budget_mode == FCS_BUDGET_LAW) {
@@ -307,7 +307,12 @@ int fcs_create(const fcs_params* p, fcs_handle* out) {
     DCell d{p->cells[i].policy, p->cells[i].arrival, p->cells[i].b_floor, p->cells[i].b_frac_thr};
     if (d.policy == FCS_POLICY_CLASSES) d.b_frac_thr = class_table_off[i];
     if (d.policy == FCS_POLICY_MC) { d.b_frac_thr = static_cast<uint32_t>(p->cells[i].assumed_o); h->has_mc = true; }
-    if (d.policy == FCS_POLICY_ALPHA) { d.b_frac_thr = static_cast<uint32_t>(p->cells[i].protect_limit); h->has_alpha = true; }
+    if (d.policy == FCS_POLICY_ALPHA) {
+      int32_t limit = 0;
+      if (fcs_protect_limit(p->cells[i].alpha, p->capacity, &limit) != FCS_OK) { delete h; return FCS_EINVAL; }
+      d.b_frac_thr = static_cast<uint32_t>(limit);
+      h->has_alpha = true;
+    }
     if (p->cells[i].budget_mode != FCS_BUDGET_SPLIT) {  // the mode rides in the bits above the policy
       d.policy |= p->cells[i].budget_mode << 8;
       if (p->cells[i].budget_mode == FCS_BUDGET_LAW) d.b_floor = p->cells[i].budget_law;
@@ -653,6 +658,13 @@ int fcs_stability_bound(const fcs_params* p, double* lambda_star) {
   }
   if (!(ew > 0.0)) return FCS_EINVAL;
   *lambda_star = static_cast<double>(p->capacity) / ew;
+  return FCS_OK;
+}
+
+int fcs_protect_limit(double alpha, int32_t capacity, int32_t* limit) {
+  if (!limit || !(alpha >= 0.0 && alpha <= 1.0) || capacity < 1 || capacity > kLimit) return FCS_EINVAL;
+  const double room = (1.0 - alpha) * static_cast<double>(capacity);
+  *limit = static_cast<int32_t>(std::floor(room));
   return FCS_OK;
 }
 

@@ -193,35 +193,54 @@ def _full_size(wl, samples, label, n_threads=16):
     return eng, got
 
 
-def test_config1_full_size_sampled_paths():
+def test_config1_full_size_every_path():
+    # all 2,048 paths of the configuration against the oracle (about ten seconds of 16 host threads)
     wl = configs.config1(oracle.stability_bound)
-    eng, got = _full_size(wl, [0, 417, 1023], "cfg1 full")
+    eng, got = _full_size(wl, np.arange(wl.n_replicas), "cfg1 full")
     R = eng.n_replicas
     assert eng.n_paths == 2048 and eng.n_steps == 100000
     assert np.array_equal(got["arrived"][:R], got["arrived"][R:])   # both policies see the same arrivals
 
 
 def test_config2_full_size_sampled_paths():
+    # 64 of the 4,096 replicas of each of the three loads, traces included
     wl = configs.config2(oracle.stability_bound)
-    eng, _ = _full_size(wl, [0, 4095], "cfg2 full")
+    eng, _ = _full_size(wl, np.arange(0, 4096, 64), "cfg2 full")
     assert eng.n_paths == 12288 and eng.n_steps == 200000
+    assert eng.trace_q is not None and eng.trace_q.shape == (12288, 200)
 
 
 def test_config3_full_size_sampled_paths():
+    # one replica of every one of the 2,048 cells of the grid, and every replica of its four corners
+    from concurrent.futures import ThreadPoolExecutor
     wl = configs.config3(oracle.stability_bound)
     eng = run(wl)
-    assert eng.n_paths == 262144 and eng.n_steps == 50000
+    assert eng.n_paths == 262144 and eng.n_steps == 50000 and eng.geometry()["lds_slots"] == 256
     got, _ = eng.stats()
     assert not np.any(got["error"])
     R = eng.n_replicas
     hist = eng.hist.cpu().numpy().view(np.uint32)
-    for ci in (0, 777, 2047):            # corners and one interior point of the (lambda, b) grid
-        ids = np.array([0, R - 1])
-        ref = oracle.run_cell(wl, ci, replica_ids=ids, n_threads=16)
+    p99, sat = eng.percentile(99, 100)
+    names = oracle.counter_names()
+
+    def check(ci, ids):
+        ids = np.asarray(ids)
+        ref = oracle.run_cell(wl, ci, replica_ids=ids, n_threads=1)
         rows = ci * R + ids
-        for name in oracle.counter_names():
+        for name in names:
             assert np.array_equal(ref["counters"][name], got[name][rows]), (ci, name)
         assert np.array_equal(ref["hist"], hist[rows]), (ci, "hist")
+        for k, r in enumerate(rows):
+            v, s = oracle.percentile_from_hist(ref["hist"][k], 99, 100, wl.hist_shift)
+            assert (v, s) == (int(p99[r]), bool(sat[r])), (ci, "p99", r)
+        return len(ids)
+
+    corners = (0, 31, 2016, 2047)
+    jobs = [(ci, [(37 * ci) % R]) for ci in range(len(wl.cells))]
+    jobs += [(ci, list(range(lo, lo + 8))) for ci in corners for lo in range(0, R, 8)]
+    with ThreadPoolExecutor(16) as ex:
+        checked = sum(ex.map(lambda j: check(*j), jobs))
+    assert checked == 2048 + 4 * R
     a = {k: v.astype(np.int64) for k, v in got.items()}
     assert np.array_equal(a["arrived"], a["completed"] + a["final_p"] + a["final_q"])
     assert np.array_equal(a["activations"], a["completed"] + a["final_p"] + a["evictions"])
@@ -229,7 +248,7 @@ def test_config3_full_size_sampled_paths():
 
 def test_config4_full_size_sampled_paths():
     wl = configs.config4(oracle.stability_bound)
-    eng, _ = _full_size(wl, [0, 511], "cfg4 full")
+    eng, _ = _full_size(wl, np.arange(0, 512, 16), "cfg4 full")
     assert eng.n_paths == 512 and eng.n_steps == 1000000
 
 

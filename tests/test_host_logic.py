@@ -48,6 +48,26 @@ def _create(wl, **kw):
     return rc
 
 
+def test_protect_limit_against_the_oracle_and_exact_arithmetic():
+    # floor((1 - alpha) M): the library's C double arithmetic, the oracle's, and exact rationals on decimal alphas
+    from fractions import Fraction
+    rng = np.random.default_rng(11)
+    for M in (20, 1500, 4000, 16492, 262144, 1 << 30):
+        for a in list(rng.random(200)) + [0.0, 1.0, 0.05, 0.1, 0.15, 0.25, 0.3, 0.999, 0.5]:
+            assert binding.protect_limit(a, M) == oracle.protect_limit(a, M), (a, M)
+    for M in (20, 16492, 100000):
+        for k in range(0, 101):
+            exact = (1 - Fraction(k, 100)) * M
+            got = binding.protect_limit(k / 100.0, M)
+            # a decimal alpha is not a binary fraction: where (1 - alpha) M is a whole number the double
+            # product may land just below it
+            assert got == exact.numerator // exact.denominator or (exact.denominator == 1 and got == exact - 1), (k, M)
+    out = C.c_int32(0)
+    for a, M in ((-0.1, 10), (1.1, 10), (float("nan"), 10), (0.5, 0), (0.5, (1 << 30) + 1)):
+        assert fcs.lib().fcs_protect_limit(a, M, C.byref(out)) == -1
+    assert fcs.lib().fcs_protect_limit(0.5, 10, None) == -1
+
+
 def test_create_validates_parameters():
     ok = configs.toy()
     assert _create(ok) == 0
@@ -82,9 +102,10 @@ def test_create_validates_the_other_policies():
     al = configs.alpha_sweep(n_replicas=2, n_steps=10)
     assert _create(al) == 0
     p, keep = fcs.binding.make_params(al)
-    p.cells[0].protect_limit = al.capacity + 1
     h = C.c_void_p()
-    assert fcs.lib().fcs_create(C.byref(p), C.byref(h)) == -1
+    for bad in (-0.01, 1.5, float("nan")):
+        p.cells[0].alpha = bad
+        assert fcs.lib().fcs_create(C.byref(p), C.byref(h)) == -1
     # MC benchmark: the slot model without chunking or token budget, an assumed length that covers every output
     ut = configs.unknown_types(n_replicas=2, n_steps=10)
     assert _create(ut) == 0
