@@ -192,6 +192,9 @@ enum {
   FCS_C_ERROR_STEP,      /* slot at which it stopped                                */
   FCS_C_ELAPSED,         /* time units the slots took (= n_steps while every slot   */
                          /* lasts one unit)                                         */
+  FCS_C_CLOCK_START,     /* device wall clock (ticks of 10 ns, the GPU's constant   */
+  FCS_C_CLOCK_END,       /* 100 MHz counter) when the path's workgroup started and  */
+                         /* ended: for profiling; not reproducible from run to run  */
   FCS_N_COUNTERS
 };
 /* Digest: h = 14695981039346656037; for each word x: h = (h ^ x) * 1099511628211.

@@ -19,6 +19,8 @@ LIB_PATH = os.path.join(_HERE, "libfcs.so")
 FCS_OK, FCS_EINVAL, FCS_ENOMEM, FCS_ESTATE, FCS_EOVERFLOW, FCS_EDEVICE = 0, -1, -2, -3, -4, -5
 POLICY_FLOW, POLICY_GREEDY = 0, 1
 FLAG_SKIP_IDLE, FLAG_GENERAL_CODE = 1, 2
+# counters that describe the run on the device, not the sample path: they differ from launch to launch
+PROFILING_COUNTERS = ("clock_start", "clock_end")
 
 
 class FcsError(RuntimeError):

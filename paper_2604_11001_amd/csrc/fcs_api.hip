@@ -22,7 +22,7 @@ struct fcs_engine {
   int32_t l_min = 1;
   std::vector<DCell> cells;
   std::vector<uint32_t> blob;  // DLaw[], DCell[], class thresholds, thresholds, guides
-  uint32_t laws_off = 0, cells_off = 0, class_off = 0;
+  uint32_t laws_off = 0, cells_off = 0, class_off = 0, sched_off = 0;
   // binding
   bool bound = false;
   void* workspace = nullptr;
@@ -327,6 +327,18 @@ int fcs_create(const fcs_params* p, fcs_handle* out) {
     if (p->cells[i].policy == FCS_POLICY_FLOW || p->cells[i].policy == FCS_POLICY_GREEDY)
       h->expected_active = std::max(h->expected_active, expected_active_of(p, p->cells[i]));
   h->blob.insert(h->blob.end(), body.begin(), body.end());
+  // the schedule area (internal layout above): before the first launch the cells are ordered by a guess of
+  // the time of a path, policy by policy and by arrival rate; from then on by what the last launch measured
+  if (h->blob.size() % 2) h->blob.push_back(0u);
+  h->sched_off = static_cast<uint32_t>(h->blob.size());
+  h->blob.resize(h->blob.size() + sched_words(p->n_cells), 0u);
+  for (int32_t i = 0; i < p->n_cells; ++i) {
+    static const double weight[] = {1.0, 1.2, 1.0, 3.0, 2.0};  // FLOW, GREEDY, CLASSES, ALPHA, MC
+    double lam, lam2;
+    law_moments(p->arrival[p->cells[i].arrival], lam, lam2);
+    const uint64_t guess = static_cast<uint64_t>(1000.0 * weight[p->cells[i].policy] * (1.0 + lam));
+    std::memcpy(h->blob.data() + h->sched_off + 2 * i, &guess, sizeof(guess));
+  }
   h->blob_bytes_padded = round_up(h->blob.size() * sizeof(uint32_t), 256);
   } catch (const std::bad_alloc&) {
     delete h;
@@ -461,7 +473,7 @@ static int run_on(fcs_engine* h, const LaunchSite& site, int64_t replica_base, i
   if (h->hist_bins == 0) kp.out.hist = nullptr;
   if (h->max_requests == 0) { kp.out.arrival_step = nullptr; kp.out.completion_step = nullptr; }
   if (h->trace_every == 0) { kp.out.trace_q = nullptr; kp.out.trace_u = nullptr; }
-  int rc = launch_sim(kp, stream);
+  int rc = launch_sim(kp, h->sched_off, stream);
   if (rc != FCS_OK) return rc;
   h->ran = true;
   h->run_replicas = n_replicas;
@@ -699,7 +711,7 @@ const char* fcs_counter_name(int i) {
       "arrived", "activations", "completed", "evictions", "overflow_steps", "sum_u", "sum_p", "sum_q",
       "decode_tokens", "prefill_tokens", "useful_tokens", "stalled", "sum_latency", "max_latency",
       "max_u", "max_p", "max_q", "final_u", "final_p", "final_q", "digest", "error", "error_step",
-      "elapsed"};
+      "elapsed", "clock_start", "clock_end"};
   return (i >= 0 && i < FCS_N_COUNTERS) ? names[i] : nullptr;
 }
 

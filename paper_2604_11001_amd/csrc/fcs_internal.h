@@ -61,6 +61,10 @@ struct KParams {
   int64_t spill_stride;       // words per path
   int32_t trace_every, n_trace, hist_bins, hist_shift, max_requests;
   int32_t n_paths;
+  // launch order of the cells (by the time their slowest path took in the launch before): the cell of the
+  // k-th group of n_replicas workgroups, and where this launch records the longest path time per cell; or null
+  const int32_t* order;
+  unsigned long long* cost;
   // pacing words ({sum of paces, paths} twice, used by alternate launches) or null
   unsigned long long* pace;
   uint32_t launch_seq;
@@ -74,8 +78,15 @@ inline int lds_words(int lcap, int class_words) {
   return kLdsWordsPerSlot * lcap + S_NFIELDS * kStackLds + kScratchWords + class_words;
 }
 
-// Defined in fcs_sim.hip; launches one single-wavefront workgroup per path.
-int launch_sim(const KParams& kp, void* stream);
+// Cells of an engine that take part in the ordering of a launch (more than that: cells run in index order).
+constexpr int kMaxOrderedCells = 8192;
+// Words of the schedule area that follows the tables in the blob: the longest path time per cell of the last two launches
+// (two arrays of 64-bit words, used by alternate launches) and the launch order of the cells.
+inline uint32_t sched_words(int n_cells) { return 5u * static_cast<uint32_t>(n_cells); }
+
+// Defined in fcs_sim.hip; launches one single-wavefront workgroup per path (and before it, for engines of
+// several cells, the kernel that orders the cells; sched_off = word offset of the schedule area in the blob).
+int launch_sim(KParams kp, uint32_t sched_off, void* stream);
 
 }  // namespace fcs
 #endif

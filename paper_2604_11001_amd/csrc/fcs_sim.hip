@@ -171,9 +171,31 @@ enum { SL_SUM_U = 0, SL_SUM_P, SL_SUM_Q, SL_DEC_TOK, SL_ACT, SL_DONE, SL_EVICT, 
 #undef FCS_KERNEL_ATTR
 #undef FCS_SKIP_IDLE
 
+
+// Orders the cells of a launch by the time their slowest path took in the launch before (longest first;
+// equal times in index order, so whatever the words hold the result is a permutation), and clears the words
+// in which this launch records its own times.  A launch lasts as long as its last path, and what sets it is
+// a few slow paths rather than the mean of a cell: workgroups are handed out in index order, so the cells
+// that hold them should start first.
+__global__ __launch_bounds__(1024) void fcs_order_kernel(uint32_t* sched, int n_cells, uint32_t seq) {
+  unsigned long long* const cost_prev = reinterpret_cast<unsigned long long*>(sched) + ((seq & 1u) ^ 1u) * n_cells;
+  unsigned long long* const cost_cur = reinterpret_cast<unsigned long long*>(sched) + (seq & 1u) * n_cells;
+  int32_t* const order = reinterpret_cast<int32_t*>(sched + 4u * n_cells);
+  for (int i = static_cast<int>(threadIdx.x); i < n_cells; i += static_cast<int>(blockDim.x)) {
+    const unsigned long long mine = cost_prev[i];
+    int rank = 0;
+    for (int j = 0; j < n_cells; ++j) {
+      const unsigned long long other = cost_prev[j];
+      rank += (other > mine || (other == mine && j < i)) ? 1 : 0;
+    }
+    order[rank] = i;
+    cost_cur[i] = 0ull;
+  }
+}
+
 }  // namespace
 
-int launch_sim(const KParams& kp, void* stream) {
+int launch_sim(KParams kp, uint32_t sched_off, void* stream) {
   const size_t lds = static_cast<size_t>(lds_words(kp.lcap, kp.class_words)) * sizeof(int32_t);
   void (*kernel)(const KParams) = kp.all_policies ? fcs_sim_all_kernel
                                   : (kp.flags & FCS_FLAG_SKIP_IDLE) ? fcs_sim_skip_kernel : fcs_sim_kernel;
@@ -181,6 +203,16 @@ int launch_sim(const KParams& kp, void* stream) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (e != hipSuccess) return FCS_EDEVICE;
+  }
+  kp.order = nullptr;
+  kp.cost = nullptr;
+  if (kp.n_cells > 1 && kp.n_cells <= kMaxOrderedCells) {
+    uint32_t* sched = const_cast<uint32_t*>(kp.blob) + sched_off;
+    hipLaunchKernelGGL(fcs_order_kernel, dim3(1), dim3(1024), 0, static_cast<hipStream_t>(stream), sched, kp.n_cells,
+                       kp.launch_seq);
+    if (hipGetLastError() != hipSuccess) return FCS_EDEVICE;
+    kp.order = reinterpret_cast<const int32_t*>(sched + 4u * kp.n_cells);
+    kp.cost = reinterpret_cast<unsigned long long*>(sched) + (kp.launch_seq & 1u) * kp.n_cells;
   }
   hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(kp.n_paths)), dim3(kWave), lds,
                      static_cast<hipStream_t>(stream), kp);
