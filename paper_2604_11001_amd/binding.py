@@ -273,8 +273,9 @@ class Engine:
         _check(lib().fcs_run_from(self._h, int(replica_base), self.n_replicas, T, seed, C.c_void_p(stream)),
                "fcs_run_from")
 
-    def stats(self, cell=-1, allow_overflow=False):
-        """fcs_stats: returns (counters dict name -> uint64 array over paths, summary dict)."""
+    def stats(self, cell=-1, allow_overflow=False, profiling=False):
+        """fcs_stats: returns (counters dict name -> uint64 array over paths, summary dict).  The counters that
+        describe the run on the device rather than the sample path (PROFILING_COUNTERS) come with profiling=True."""
         L = lib()
         nc = L.fcs_n_counters()
         host = np.zeros((self.n_paths, nc), np.uint64)
@@ -283,7 +284,8 @@ class Engine:
         if rc != FCS_OK and not (allow_overflow and rc == FCS_EOVERFLOW):
             raise FcsError(rc, "fcs_stats")
         names = counter_names()
-        return {n: host[:, i].copy() for i, n in enumerate(names)}, s.as_dict()
+        return ({n: host[:, i].copy() for i, n in enumerate(names) if profiling or n not in PROFILING_COUNTERS},
+                s.as_dict())
 
     def percentile(self, num, den):
         val = np.zeros(self.n_paths, np.int32)
