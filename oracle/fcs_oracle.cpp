@@ -24,7 +24,8 @@
 //                             go back to the waiting queue.
 //                     MC    : memory-check benchmark of Section 4.1: first come first served, the
 //                             head moves only if the memory stays within M in every future slot
-//                             when all requests are taken to produce the longest possible output.
+//                             when all requests are taken to produce the longest possible output
+//                             (unknown request types), or each its own output (known types).
 //                     CLASSES: Algorithm 1 (known lengths): every class k has its own arrival
 //                             stream n_{t,k}, its own FIFO and an integer budget b_k; in
 //                             class order, min(b_k, |Q_k|) head requests of class k move
@@ -65,7 +66,8 @@
 // Slots of variable duration (time_c0, time_cp, time_cd) are a linear stand-in for the batch times of
 // Section 4.2, which the paper takes from a simulator: the form is this oracle's choice.
 // The MC rule as a whole is a reading of one sentence of Section 4.1 (the rule comes from a cited
-// paper): usage checked in every future slot, all outputs taken as one common longest length.
+// paper): usage checked in every future slot, all outputs taken as one common longest length, or,
+// with known request types, each as what it is.
 #include <algorithm>
 #include <atomic>
 #include <cstdint>
@@ -118,7 +120,7 @@ struct fo_config {
   fo_law budget_law;      // mode 1: B_t = lo + #{thr <= word 1}
   int64_t budget_b16;     // mode 2: b in units of 2^-16; B_t = floor(t b) - floor((t - 1) b)
   // MC only
-  int64_t assumed_o;      // output length every request is taken to reach in the prediction
+  int64_t assumed_o;      // output length every request is taken to reach in the prediction; 0: its own (known types)
   // Slots of variable duration (all three 0: every slot lasts one unit).  Time runs in units of the
   // arrival law: n_u requests arrive in unit u; slot t starts at time tau_t (tau_1 = 1), sees the
   // arrivals of the units up to tau_t, and lasts d_t = c0 + cp (prompt tokens it processed) + cd
@@ -379,17 +381,19 @@ void simulate(const fo_config& cfg, int64_t replica, int64_t T, uint64_t seed, i
       // was, or is now, activated: no chunking and no token budget under this policy), holds
       // l + (tokens so far) and leaves after its last one.  The usage only drops when somebody
       // leaves, so the slots to look at are the last slots of the requests.
-      const int64_t o_hat = cfg.assumed_o;
+      // With known request types (assumed_o = 0) each request is predicted to produce its own o tokens;
+      // with unknown types all of them the one length assumed_o.
+      auto predicted = [&](const Request& r) { return cfg.assumed_o > 0 ? cfg.assumed_o : r.o; };
       auto fits_in_future = [&](const Request& c) {
-        struct Pred { int64_t l, s; };
+        struct Pred { int64_t l, s, o_hat; };
         std::vector<Pred> S;
-        for (const Request& r : P) S.push_back({r.l, t - r.j});  // j tokens by slot t - 1: the first came in t - j
-        S.push_back({c.l, t});
+        for (const Request& r : P) S.push_back({r.l, t - r.j, predicted(r)});  // j tokens by slot t - 1: the first came in t - j
+        S.push_back({c.l, t, predicted(c)});
         for (const Pred& k : S) {
-          const int64_t u = k.s + o_hat - 1;  // k's last slot
+          const int64_t u = k.s + k.o_hat - 1;  // k's last slot
           int64_t use = 0;
           for (const Pred& i : S)
-            if (i.s + o_hat - 1 >= u) use += i.l + std::min(o_hat, u - i.s + 1);
+            if (i.s + i.o_hat - 1 >= u) use += i.l + std::min(i.o_hat, u - i.s + 1);
           if (use > M) return false;
         }
         return true;
@@ -558,11 +562,13 @@ int fo_run(const fo_config* cfg, int64_t n_ids, const int64_t* replica_ids, int6
   if (!cfg || !out || !out->counters || n_ids < 0 || n_steps < 0) return -1;
   if (cfg->policy < 0 || cfg->policy > 4) return -1;
   if (cfg->policy == 4) {  // the prediction is that of the slot model without chunking or token budget
-    if (cfg->assumed_o < 1 || cfg->token_budget < (1ll << 30)) return -1;
+    if (cfg->assumed_o < 0 || cfg->token_budget < (1ll << 30)) return -1;
     for (int32_t k = 0; k < cfg->n_classes; ++k) {
       if (cfg->prompt[k].lo + cfg->prompt[k].n_thr > cfg->prefill_chunk) return -1;
-      if (cfg->decode[k].lo + cfg->decode[k].n_thr > cfg->assumed_o) return -1;
-      if (cfg->prompt[k].lo + cfg->prompt[k].n_thr + cfg->assumed_o > cfg->capacity) return -1;
+      // unknown types: the one assumed length covers every output; known types (0): the longest output itself
+      const int64_t longest = cfg->assumed_o > 0 ? cfg->assumed_o : cfg->decode[k].lo + cfg->decode[k].n_thr;
+      if (cfg->decode[k].lo + cfg->decode[k].n_thr > longest) return -1;
+      if (cfg->prompt[k].lo + cfg->prompt[k].n_thr + longest > cfg->capacity) return -1;
     }
   }
   if (cfg->policy == 3 && (cfg->protect_limit < 0 || cfg->protect_limit > cfg->capacity)) return -1;

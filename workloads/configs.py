@@ -123,6 +123,12 @@ def mc_cell(arrival: int, assumed_o: int, label: str = "") -> Cell:
     return Cell(MC, arrival, 0, 0, label or f"mc(o_hat={assumed_o})", assumed_o=int(assumed_o))
 
 
+def mc_known_cell(arrival: int, label: str = "mc(known types)") -> Cell:
+    """The memory-check benchmark with known request types (Section 4.1, first study): every request is
+    predicted to produce its own output length."""
+    return Cell(MC, arrival, 0, 0, label, assumed_o=0)
+
+
 def longest_output(mixture: Mixture) -> int:
     return max(c.decode.hi for c in mixture.classes)
 
