@@ -131,7 +131,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=DEFAULT_CONFIG,
                     help="index of the benchmark configuration of the timed line (default 3, the parameter grid)")
     ap.add_argument("--workload", choices=("known-classes", "alpha-sweep", "budget-forms", "unknown-types",
-                                           "timed-study"),
+                                           "known-types", "timed-study"),
                     default=None,
                     help="instead of --config: known-classes = the known-lengths study of Section 4.1 under "
                          "Algorithm 1 (three classes, Poisson rate 5 and budget 4 each, M = 16492); alpha-sweep = "
@@ -139,7 +139,9 @@ def main() -> int:
                          "for four values of alpha, and the greedy baseline; budget-forms = configuration 1's "
                          "workload under Algorithm 2 with three forms of the activation budget B_t; "
                          "unknown-types = Section 4.1's three classes with unknown types under Algorithm 2, "
-                         "alpha-protection, the MC benchmark and greedy; timed-study = configuration 1's "
+                         "alpha-protection, the MC benchmark and greedy; known-types = the same classes with "
+                         "known types under Algorithm 1, alpha-protection, the MC benchmark with every request "
+                         "predicted at its own length, and greedy; timed-study = configuration 1's "
                          "mix under Algorithm 2 and greedy with slots of variable duration")
     ap.add_argument("--replicas", type=int, default=None)
     ap.add_argument("--slots", type=int, default=None)
@@ -181,6 +183,8 @@ def main() -> int:
             w = configs.budget_forms(bound)
         elif args.workload == "unknown-types":
             w = configs.unknown_types()
+        elif args.workload == "known-types":
+            w = configs.known_types()
         elif args.workload == "timed-study":
             w = configs.timed_study(bound)
         else:

@@ -36,6 +36,7 @@ struct fcs_engine {
   bool has_alpha = false;  // ALPHA cells: an overflow sends the whole active set to the evicted stack
   bool has_budget_modes = false;  // FLOW cells whose B_t is not the Bernoulli split
   bool has_mc = false;
+  int32_t wheel_slots = 0;  // MC cells with known request types: slots of the departure wheel (else 0)
   int32_t time_c0 = 0, time_cp = 0, time_cd = 0;
   int32_t flags = 0;
   int64_t classes_active = 0;  // CLASSES: most requests active at once when no prefill ever waits
@@ -91,11 +92,15 @@ bool params_ok(const fcs_params* p) {
     const fcs_cell& c = p->cells[i];
     if (c.policy < FCS_POLICY_FLOW || c.policy > FCS_POLICY_MC) return false;
     if (c.policy == FCS_POLICY_MC) {  // the prediction is that of the slot model without chunking or token budget
-      if (c.assumed_o < o_max || p->token_budget < kLimit || p->prefill_chunk < l_max) return false;
-      if (static_cast<int64_t>(l_max) + c.assumed_o > p->capacity) return false;
+      if (p->token_budget < kLimit || p->prefill_chunk < l_max) return false;
+      // assumed_o = 0: known request types, every request predicted at its own length (one wheel entry per
+      // future slot up to the longest output); else one common length that covers every output
+      if (c.assumed_o == 0 ? o_max > kMaxWheelSlots : c.assumed_o < o_max) return false;
+      const int64_t longest = c.assumed_o == 0 ? o_max : c.assumed_o;
+      if (static_cast<int64_t>(l_max) + longest > p->capacity) return false;
       // the kernel sums l + j + o_hat over the active set in 32 bits
       const int64_t most_active = p->max_active > 0 ? p->max_active : 8192;
-      if ((l_max + 2 * static_cast<int64_t>(c.assumed_o)) * most_active >= (1ll << 31)) return false;
+      if ((l_max + 2 * longest) * most_active >= (1ll << 31)) return false;
     }
     if (c.policy == FCS_POLICY_ALPHA && !(c.alpha >= 0.0 && c.alpha <= 1.0)) return false;
     if (c.budget_mode < FCS_BUDGET_SPLIT || c.budget_mode > FCS_BUDGET_CREDIT) return false;
@@ -246,6 +251,12 @@ double expected_active_of(const fcs_params* p, const fcs_cell& c) {
   return std::min(by_rate, by_memory);
 }
 
+// LDS words of a path beyond its active set, stack and scratch: the per-class tables of CLASSES cells and
+// the departure wheel of MC cells with known request types (two words per slot)
+int extra_lds_words(const fcs_engine* h) {
+  return (h->has_classes ? class_lds_words(h->n_classes) : 0) + 2 * h->wheel_slots;
+}
+
 int sync_last(fcs_engine* h) {
   return hipStreamSynchronize(static_cast<hipStream_t>(h->run_stream)) == hipSuccess ? FCS_OK : FCS_EDEVICE;
 }
@@ -306,7 +317,16 @@ int fcs_create(const fcs_params* p, fcs_handle* out) {
   for (int32_t i = 0; i < p->n_cells; ++i) {
     DCell d{p->cells[i].policy, p->cells[i].arrival, p->cells[i].b_floor, p->cells[i].b_frac_thr};
     if (d.policy == FCS_POLICY_CLASSES) d.b_frac_thr = class_table_off[i];
-    if (d.policy == FCS_POLICY_MC) { d.b_frac_thr = static_cast<uint32_t>(p->cells[i].assumed_o); h->has_mc = true; }
+    if (d.policy == FCS_POLICY_MC) {
+      d.b_frac_thr = static_cast<uint32_t>(p->cells[i].assumed_o);
+      h->has_mc = true;
+      if (p->cells[i].assumed_o == 0) {
+        int64_t o_max = 0;
+        for (int32_t c = 0; c < p->n_classes; ++c)
+          o_max = std::max<int64_t>(o_max, static_cast<int64_t>(p->decode[c].lo) + p->decode[c].n_thr);
+        h->wheel_slots = static_cast<int32_t>(round_up(static_cast<size_t>(o_max), kWave));
+      }
+    }
     if (d.policy == FCS_POLICY_ALPHA) {
       int32_t limit = 0;
       if (fcs_protect_limit(p->cells[i].alpha, p->capacity, &limit) != FCS_OK) { delete h; return FCS_EINVAL; }
@@ -372,7 +392,7 @@ static int geometry_for(fcs_engine* h, int64_t n_replicas, int32_t* lcap, int32_
     int64_t per_cu = (n_paths + 255) / 256;
     per_cu = std::min<int64_t>(std::max<int64_t>(per_cu, 4), 8);
     const int64_t words = (160 * 1024 / per_cu) / 4 - S_NFIELDS * kStackLds - kScratchWords -
-                          (h->has_classes ? class_lds_words(h->n_classes) : 0);
+                          extra_lds_words(h);
     lc = static_cast<int32_t>(words / kLdsWordsPerSlot / kLdsBlock * kLdsBlock);
     lc = std::min(std::max(lc, kLdsBlock), 2048);
   }
@@ -449,6 +469,7 @@ static int run_on(fcs_engine* h, const LaunchSite& site, int64_t replica_base, i
   kp.seed_hi = static_cast<uint32_t>(seed >> 32);
   kp.lcap = site.lcap; kp.hcap = site.hcap; kp.hscap = site.hscap;
   kp.class_words = h->has_classes ? class_lds_words(h->n_classes) : 0;
+  kp.wheel_slots = h->wheel_slots;
   kp.all_policies = (h->has_classes || h->has_alpha || h->has_budget_modes || h->has_mc || h->time_c0 != 0) ? 1 : 0;
   kp.time_c0 = h->time_c0; kp.time_cp = h->time_cp; kp.time_cd = h->time_cd;
   kp.flags = h->flags;
@@ -685,7 +706,7 @@ int fcs_geometry(fcs_handle h, int32_t* lds_slots, int32_t* lds_bytes, int32_t* 
   if (!h->bound && !h->ran) return FCS_ESTATE;
   const int32_t lc = h->ran ? h->run_lcap : h->lcap, hc = h->ran ? h->run_hcap : h->hcap;
   if (lds_slots) *lds_slots = lc;
-  if (lds_bytes) *lds_bytes = lds_words(lc, h->has_classes ? class_lds_words(h->n_classes) : 0) * 4;
+  if (lds_bytes) *lds_bytes = lds_words(lc, extra_lds_words(h)) * 4;
   if (spill_slots) *spill_slots = hc;
   return FCS_OK;
 }

@@ -42,6 +42,7 @@ constexpr int kCompactSlack = 64;    // compact when this many dead slots have a
 constexpr int kLdsCompactMin = 16;   // ... or this many when the next slot would be the first outside LDS
 constexpr int kMaxCountThr = 63;
 constexpr int kMaxClasses = 16;
+constexpr int kMaxWheelSlots = 1024;  // longest output under the MC benchmark with known request types
 
 struct KParams {
   const uint32_t* blob;
@@ -54,6 +55,8 @@ struct KParams {
   uint32_t seed_lo, seed_hi;
   int32_t lcap, hcap, hscap;  // LDS slots, spill slots, spill stack entries (per path)
   int32_t class_words;        // LDS words of the per-class tables (0 without CLASSES cells)
+  int32_t wheel_slots;        // MC cells with known request types: future slots that the wheel of predicted
+                              // departures spans (a multiple of 64, at least the longest output; else 0)
   int32_t all_policies;       // some cell is neither FLOW nor GREEDY: run the kernel built with all policies
   int32_t time_c0, time_cp, time_cd;  // slots of variable duration (all-policies kernel), else 0
   int32_t flags;              // FCS_FLAG_*

@@ -196,7 +196,7 @@ __global__ __launch_bounds__(1024) void fcs_order_kernel(uint32_t* sched, int n_
 }  // namespace
 
 int launch_sim(KParams kp, uint32_t sched_off, void* stream) {
-  const size_t lds = static_cast<size_t>(lds_words(kp.lcap, kp.class_words)) * sizeof(int32_t);
+  const size_t lds = static_cast<size_t>(lds_words(kp.lcap, kp.class_words + 2 * kp.wheel_slots)) * sizeof(int32_t);
   void (*kernel)(const KParams) = kp.all_policies ? fcs_sim_all_kernel
                                   : (kp.flags & FCS_FLAG_SKIP_IDLE) ? fcs_sim_skip_kernel : fcs_sim_kernel;
   if (lds > 48 * 1024) {

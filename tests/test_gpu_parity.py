@@ -10,7 +10,7 @@ import oracle
 import paper_2604_11001_amd as fcs
 from workloads import FLOW, GREEDY, configs, laws
 from workloads.configs import (Workload, alpha_cell, flow_cell, flow_credit_cell, flow_law_cell, greedy_cell,
-                               longest_output, mc_cell)
+                               longest_output, mc_cell, mc_known_cell)
 
 from parity_util import check_summary, compare
 
@@ -415,7 +415,16 @@ def test_mc_benchmark_cases():
         # hundreds of active requests: the prediction runs over several passes of 64 slots
         "large active set": mk("mc-large", small, 45000, 9.0, 1500, (mc_cell(0, 150), mc_cell(0, 300)), R=3),
         "memory for one request": mk("mc-one", laws.single(laws.uniform_int(2, 5), laws.uniform_int(1, 7)), 12, 0.4,
-                                     800, (mc_cell(0, 7),)),
+                                     800, (mc_cell(0, 7), mc_known_cell(0))),
+        # known request types (every request predicted at its own length) beside the longest-length rule
+        "known types, overloaded": mk("mc-known-over", mix, 1500, 2.0, 2000, (mc_known_cell(0), mc_cell(0, 100))),
+        "known types, two classes": mk("mc-known-two", two, 5000, 1.2, 2500, (mc_known_cell(0), flow_cell(0, 1.5))),
+        "known types, one length": mk("mc-known-exact", laws.single(laws.uniform_int(3, 12), laws.point(30)), 1200,
+                                      3.0, 1500, (mc_known_cell(0), mc_cell(0, 30))),
+        # outputs up to 700 slots: the wheel of predicted departures spans eleven passes of 64 slots
+        "known types, long outputs": mk("mc-known-long", laws.single(laws.uniform_int(1, 6), laws.geometric(120.0, cap=700)),
+                                        30000, 1.5, 3000, (mc_known_cell(0),), R=3),
+        "known types, large active set": mk("mc-known-large", small, 45000, 9.0, 1500, (mc_known_cell(0),), R=3),
     }
     for label, wl in cases.items():
         eng = run(wl)
@@ -425,8 +434,12 @@ def test_mc_benchmark_cases():
         mc_rows = np.concatenate([np.arange(i * R, (i + 1) * R) for i, c in enumerate(wl.cells) if c.policy == 4])
         assert not got["evictions"][mc_rows].any() and not got["overflow_steps"][mc_rows].any(), label
         assert np.all(got["max_u"][mc_rows] <= wl.capacity), label
-        if label == "large active set":
+        if label in ("large active set", "known types, large active set"):
             assert got["max_p"][:R].min() > 200
+        if label == "known types, one length":   # all outputs equal: the two rules coincide
+            assert all(np.array_equal(got[k][:R], got[k][R:]) for k in got)
+        if label == "known types, overloaded":   # knowing the lengths admits more
+            assert got["completed"][:R].sum() > got["completed"][R:].sum()
         if label == "room for everybody":
             assert all(np.array_equal(got[k][:R], got[k][R:]) for k in got)
 
@@ -499,6 +512,20 @@ def test_unknown_types_scaled_and_full_size_sampled_paths():
     assert got["sum_q"][mc].sum() > 100 * got["sum_q"][:R].sum()    # the longest-length prediction admits too little
 
 
+def test_known_types_scaled_and_full_size_sampled_paths():
+    # Section 4.1, known request types: Algorithm 1, alpha-protection, MC (own lengths) and greedy
+    wl = configs.known_types(n_replicas=6, n_steps=3000, trace_every=100, hist_bins=1024, max_requests=1 << 15)
+    compare(run(wl), wl, label="known types scaled")
+    wl = configs.known_types()
+    eng, got = _full_size(wl, [0, 511, 1023], "known types full", n_threads=16)
+    assert eng.n_paths == 4 * 1024 and eng.n_steps == 10000
+    R = eng.n_replicas
+    a1, mc = slice(0, R), slice(2 * R, 3 * R)
+    assert not got["evictions"][a1].any() and not got["overflow_steps"][a1].any()     # Theorem 1 holds here
+    assert np.all(got["max_u"][a1] <= 4 * (410 + 1220 + 2430))
+    assert not got["evictions"][mc].any() and np.all(got["max_u"][mc] <= wl.capacity)
+
+
 # ---- seeded random small workloads over every policy, budget form and tier ---------------------------------
 
 def _random_workload(rng, k):
@@ -530,8 +557,8 @@ def _random_workload(rng, k):
     cells = (flow_cell(0, float(rng.uniform(0.1, 3.0))), greedy_cell(0), alpha_cell(0, float(rng.uniform(0.0, 0.6))),
              flow_law_cell(0, 1), flow_credit_cell(0, float(rng.uniform(0.05, 3.0))))
     if tau == INF and chunk >= l_hi:   # the MC benchmark is defined on the slot model without chunking or budget
-        cells += (mc_cell(0, decode.hi), mc_cell(0, decode.hi + int(rng.integers(1, 50))))
-        M = max(M, l_hi + cells[-1].assumed_o)
+        cells += (mc_cell(0, decode.hi), mc_cell(0, decode.hi + int(rng.integers(1, 50))), mc_known_cell(0))
+        M = max(M, l_hi + cells[-2].assumed_o)
     time_model = (0, 0, 0)
     if k % 5 == 3:   # slots of variable duration; the arrival rate is per time unit, so it shrinks with them
         time_model = (int(rng.integers(1, 6)), int(rng.integers(0, 3)), int(rng.integers(0, 3)))

@@ -113,6 +113,9 @@ def test_create_validates_the_other_policies():
     assert _create(ut.scaled(token_budget=4096)) == -1
     assert _create(ut.scaled(cells=(configs.mc_cell(0, 59),))) == -1     # a class produces 60 tokens
     assert _create(ut.scaled(cells=(configs.mc_cell(0, 60),), capacity=69)) == -1
+    assert _create(ut.scaled(cells=(configs.mc_known_cell(0),))) == 0        # known request types
+    long_out = laws.single(laws.point(10), laws.uniform_int(1, 1025))
+    assert _create(ut.scaled(cells=(configs.mc_known_cell(0),), mixture=long_out)) == -1   # outputs beyond the wheel
     # slots of variable duration: c0 >= 1, not with Algorithm 1 cells
     toy = configs.toy()
     assert _create(toy.scaled(time_model=(2, 1, 1))) == 0

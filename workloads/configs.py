@@ -298,6 +298,21 @@ def unknown_types(lam_per_class: float = 3.3, b: float = 11.0, alpha: float = 0.
         n_steps=n_steps, seed=seed, **kw)
 
 
+def known_types(lam_per_class: float = 3.3, budgets=(4, 4, 4), alpha: float = 0.05, capacity: int = 16492,
+                n_replicas: int = 1024, n_steps: int = 10_000, seed: int = 14, **kw) -> Workload:
+    """The paper's synthetic study with known request types (Section 4.1, first row of its figure): classes
+    (10, 20), (10, 40), (10, 60), Poisson arrivals per class, M = 16492, under Algorithm 1 with b = (4, 4, 4),
+    the alpha-protection greedy baseline, the MC benchmark with every request predicted at its own length, and
+    the greedy / evict-newest baseline.  Algorithm 1 draws one arrival stream per class; the other three share
+    one stream of the summed rate whose requests fall into the classes with equal shares."""
+    cls = tuple(RequestClass(1.0, laws.point(10), laws.point(o)) for o in (20, 40, 60))
+    arr = (laws.poisson_counts(lam_per_class), laws.poisson_counts(3.0 * lam_per_class))
+    cells = (classes_cell([0, 0, 0], budgets), alpha_cell(1, alpha), mc_known_cell(1), greedy_cell(1))
+    return Workload(
+        name="known-types", capacity=capacity, token_budget=1 << 30, prefill_chunk=1 << 30, mixture=Mixture(cls),
+        arrival_laws=arr, cells=cells, n_replicas=n_replicas, n_steps=n_steps, seed=seed, **kw)
+
+
 def timed_study(bound: Bound, time_model=(40, 1, 1), n_replicas: int = 1024, n_steps: int = 10_000) -> Workload:
     """Configuration 1's request mix and memory under Algorithm 2 and the greedy baseline with slots of variable
     duration (a linear stand-in for the batch times of Section 4.2): a slot lasts 40 + prompt tokens + output
