@@ -17,7 +17,8 @@ SOURCES = ["fcs_api.hip", "fcs_sim.hip"]
 # memory round trips on a path's instruction chain).
 RESOURCE_LIMITS = {"fcs_sim_kernel": {"VGPRs": 128, "ScratchSize [bytes/lane]": 0},
                    "fcs_sim_skip_kernel": {"VGPRs": 128, "ScratchSize [bytes/lane]": 0},
-                   "fcs_sim_all_kernel": {"VGPRs": 256, "ScratchSize [bytes/lane]": 0}}
+                   "fcs_sim_all_kernel": {"VGPRs": 256, "ScratchSize [bytes/lane]": 0},
+                   "fcs_sim_mck_kernel": {"VGPRs": 256, "ScratchSize [bytes/lane]": 0}}
 
 
 def kernel_resources(remarks: str) -> dict:

@@ -145,6 +145,7 @@ enum { SL_SUM_U = 0, SL_SUM_P, SL_SUM_Q, SL_DEC_TOK, SL_ACT, SL_DONE, SL_EVICT, 
 // SIMD (the fixed registers of the assembly loop are v84-v127): with 256 LDS slots per path a compute unit
 // then holds 16 paths, which is what hides the latencies of a path's instruction chain best.
 #define FCS_ALL_POLICIES 0
+#define FCS_MC_KNOWN 0
 #define FCS_SKIP_IDLE 0
 #define FCS_KERNEL fcs_sim_kernel
 #define FCS_KERNEL_ATTR __attribute__((amdgpu_waves_per_eu(4, 4)))
@@ -166,10 +167,18 @@ enum { SL_SUM_U = 0, SL_SUM_P, SL_SUM_Q, SL_DEC_TOK, SL_ACT, SL_DONE, SL_EVICT, 
 #define FCS_KERNEL fcs_sim_all_kernel
 #define FCS_KERNEL_ATTR
 #include "fcs_sim_kernel.inc"
+#undef FCS_KERNEL
+#undef FCS_MC_KNOWN
+
+// the same with the MC benchmark for known request types
+#define FCS_MC_KNOWN 1
+#define FCS_KERNEL fcs_sim_mck_kernel
+#include "fcs_sim_kernel.inc"
 #undef FCS_ALL_POLICIES
 #undef FCS_KERNEL
 #undef FCS_KERNEL_ATTR
 #undef FCS_SKIP_IDLE
+#undef FCS_MC_KNOWN
 
 
 // Orders the cells of a launch by the time their slowest path took in the launch before (longest first;
@@ -197,7 +206,7 @@ __global__ __launch_bounds__(1024) void fcs_order_kernel(uint32_t* sched, int n_
 
 int launch_sim(KParams kp, uint32_t sched_off, void* stream) {
   const size_t lds = static_cast<size_t>(lds_words(kp.lcap, kp.class_words + 2 * kp.wheel_slots)) * sizeof(int32_t);
-  void (*kernel)(const KParams) = kp.all_policies ? fcs_sim_all_kernel
+  void (*kernel)(const KParams) = kp.all_policies ? (kp.wheel_slots > 0 ? fcs_sim_mck_kernel : fcs_sim_all_kernel)
                                   : (kp.flags & FCS_FLAG_SKIP_IDLE) ? fcs_sim_skip_kernel : fcs_sim_kernel;
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
