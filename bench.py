@@ -63,7 +63,7 @@ def cpu_baseline(wl, target_seconds: float = 15.0):
     t0 = time.perf_counter()
     rs_cal = run_cells(cal, [0])
     dt_cal = max(time.perf_counter() - t0, 1e-3)
-    threads_cal = len(cal) if len(cal) >= cores else cores
+    threads_cal = cores if len(cal) >= cores else 1                 # one replica per call: one thread at a time
     per_replica = rs_cal / len(cal) * n_cells                       # request-steps of one replica of every cell
     rate = rs_cal / dt_cal * cores / max(threads_cal, 1)            # what all host threads together may reach
     k = int(max(1, min(wl.n_replicas, round(target_seconds * rate / max(per_replica, 1.0)))))
@@ -153,6 +153,9 @@ def main() -> int:
     ap.add_argument("--skip-idle", action="store_true",
                     help="event skipping: runs of slots without arrival, admission, prefill or completion are "
                          "advanced in one go (same results; reported apart from the step-synchronous line)")
+    ap.add_argument("--path-times", action="store_true",
+                    help="profiling aid: per cell, when the workgroups of its paths started and how long they took "
+                         "in the last timed launch (from the device-clock counters), as path_times in the line")
     ap.add_argument("--cells", type=str, default="", help="profiling aid: comma-separated subset of the cells")
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="profiling aid: first run a plain device copy of this many MiB (scale for HBM counters)")
@@ -205,19 +208,32 @@ def main() -> int:
         wall, kernel_ms = time_passes(torch, eng, steps, warmup)
         _, summary = eng.stats()
         n_paths = eng.n_paths
+        times = None
+        if args.path_times:
+            import numpy as np
+            ctr, _ = eng.stats(profiling=True)
+            start, end = ctr["clock_start"].astype(np.int64), ctr["clock_end"].astype(np.int64)
+            t0, tick_ms = start.min(), 1e-5            # the device wall clock runs at 100 MHz
+            times = {"launch_ms": float((end.max() - t0) * tick_ms), "cells": []}
+            for ci in range(len(w.cells)):
+                rows = slice(ci * eng.n_replicas, (ci + 1) * eng.n_replicas)
+                d, b = (end[rows] - start[rows]) * tick_ms, (start[rows] - t0) * tick_ms
+                times["cells"].append({"cell": ci, "label": w.cells[ci].label, "start_ms": [float(b.min()), float(b.max())],
+                                       "duration_ms": {"mean": float(d.mean()), "p50": float(np.median(d)),
+                                                       "p99": float(np.quantile(d, 0.99)), "max": float(d.max())}})
         eng.close()
         del eng
         torch.cuda.empty_cache()
         avg_ms = sum(kernel_ms) / len(kernel_ms)
         rs = int(summary["request_steps"])
         return {"wall": wall, "kernel_ms": avg_ms, "request_steps": rs, "geo": geo, "summary": summary,
-                "paths": n_paths,
+                "paths": n_paths, "path_times": times,
                 "achieved_gbs": rs * BYTES_PER_REQUEST_STEP / (avg_ms * 1e-3) / 1e9,
                 "clocks_per_slot_and_simd": avg_ms * 1e-3 * CLOCK_HZ * N_SIMD / (n_paths * w.n_steps)}
 
     wl = build(fcs.stability_bound)
     plain = not (args.cells or args.replicas or args.slots or args.workload or args.lds_slots or args.max_active
-                 or args.skip_idle)
+                 or args.skip_idle or args.path_times)
     if args.workload:
         wl_label, kernel = args.workload, "fcs_sim_all_kernel"
     else:
@@ -283,6 +299,8 @@ def main() -> int:
                    "skip_idle": bool(args.skip_idle)},
         "roofline": roof,
     }
+    if m["path_times"] is not None:
+        line["path_times"] = m["path_times"]
     if plain and not args.no_all_configs:
         # the other benchmark configurations, one warm-up and two timed passes each, same accounting
         rows = []
