@@ -29,7 +29,7 @@ struct fcs_engine {
   size_t workspace_bytes = 0;
   int64_t bound_replicas = 0;
   fcs_outputs out{};
-  int32_t lcap = 0, hcap = 0, hscap = 0;
+  int32_t lcap = 0, hcap = 0, hscap = 0, stack_lds = 0;
   int64_t spill_stride = 0;
   uint32_t launch_seq = 0;
   bool has_classes = false;
@@ -46,7 +46,7 @@ struct fcs_engine {
   bool ran = false;
   int64_t run_replicas = 0, run_steps = 0;
   void* run_stream = nullptr;
-  int32_t run_lcap = 0, run_hcap = 0;
+  int32_t run_lcap = 0, run_hcap = 0, run_stack_lds = 0;
   fcs_outputs run_out{};  // the output arrays that run wrote (those of fcs_bind, or of fcs_run_static)
   uint64_t uid = 0;       // distinguishes handles that follow each other at one address
 };
@@ -368,7 +368,8 @@ int fcs_create(const fcs_params* p, fcs_handle* out) {
   return FCS_OK;
 }
 
-static int geometry_for(fcs_engine* h, int64_t n_replicas, int32_t* lcap, int32_t* hcap, int32_t* hscap) {
+static int geometry_for(fcs_engine* h, int64_t n_replicas, int32_t* lcap, int32_t* hcap, int32_t* hscap,
+                        int32_t* stack_lds) {
   if (n_replicas < 1) return FCS_EINVAL;
   const int64_t n_paths = n_replicas * h->n_cells;
   if (n_paths > (1ll << 30)) return FCS_EINVAL;
@@ -391,7 +392,7 @@ static int geometry_for(fcs_engine* h, int64_t n_replicas, int32_t* lcap, int32_
     // the hand-scheduled slot loop)
     int64_t per_cu = (n_paths + 255) / 256;
     per_cu = std::min<int64_t>(std::max<int64_t>(per_cu, 4), 8);
-    const int64_t words = (160 * 1024 / per_cu) / 4 - S_NFIELDS * kStackLds - kScratchWords -
+    const int64_t words = (160 * 1024 / per_cu) / 4 - S_NFIELDS * kStackLdsMin - kScratchWords -
                           extra_lds_words(h);
     lc = static_cast<int32_t>(words / kLdsWordsPerSlot / kLdsBlock * kLdsBlock);
     lc = std::min(std::max(lc, kLdsBlock), 2048);
@@ -399,16 +400,29 @@ static int geometry_for(fcs_engine* h, int64_t n_replicas, int32_t* lcap, int32_
   lc = static_cast<int32_t>(std::min<int64_t>(lc, static_cast<int64_t>(round_up(max_active, kLdsBlock))));
   *lcap = lc;
   *hcap = static_cast<int32_t>(std::max<int64_t>(max_active - lc, 0));
+  // A compute unit hands its 160 KB of LDS out in 128 granules of 1,280 bytes (measured: 15,360 bytes per
+  // workgroup run ten to a unit, 15,616 nine), and the FLOW/GREEDY kernels fit 16 wavefronts, the others 12.
+  // The LDS part of the evicted stack takes what is left of the last granule without costing a resident
+  // path: 48 entries with 512 slots (15 KB, ten paths per unit), 128 with 256 slots (16 paths).
+  const int64_t fixed_bytes = 4 * (static_cast<int64_t>(kLdsWordsPerSlot) * lc + kScratchWords + extra_lds_words(h));
+  const int64_t wave_cap = plain ? 16 : 12;
+  auto resident = [&](int64_t stack) {
+    const int64_t granules = (fixed_bytes + 4 * S_NFIELDS * stack + 1279) / 1280;
+    return std::min<int64_t>(128 / std::max<int64_t>(granules, 1), wave_cap);
+  };
+  int32_t stack = kStackLdsMin;
+  while (stack + 16 <= kStackLdsMax && resident(stack + 16) == resident(kStackLdsMin)) stack += 16;
+  *stack_lds = stack;
   // the evicted stack holds what was evicted and not yet activated again; under ALPHA that can be a
   // whole active set on top of the rest of an earlier one
-  *hscap = static_cast<int32_t>(std::max<int64_t>((h->has_alpha ? 2 : 1) * max_active - kStackLds, 0));
+  *hscap = static_cast<int32_t>(std::max<int64_t>((h->has_alpha ? 2 : 1) * max_active - stack, 0));
   return FCS_OK;
 }
 
 int fcs_workspace_bytes(fcs_handle h, int64_t n_replicas, size_t* bytes) {
   if (!h || !bytes) return FCS_EINVAL;
-  int32_t lc, hc, hs;
-  int rc = geometry_for(h, n_replicas, &lc, &hc, &hs);
+  int32_t lc, hc, hs, sl;
+  int rc = geometry_for(h, n_replicas, &lc, &hc, &hs, &sl);
   if (rc != FCS_OK) return rc;
   const size_t stride = static_cast<size_t>(kSpillWordsPerSlot) * hc + static_cast<size_t>(S_NFIELDS) * hs;
   *bytes = h->blob_bytes_padded + round_up(stride * sizeof(int32_t) * n_replicas * h->n_cells, 256) + 256;
@@ -422,7 +436,7 @@ int fcs_bind(fcs_handle h, void* ws, size_t bytes, int64_t n_replicas, const fcs
   int rc = fcs_workspace_bytes(h, n_replicas, &need);
   if (rc != FCS_OK) return rc;
   if (bytes < need) return FCS_ENOMEM;
-  rc = geometry_for(h, n_replicas, &h->lcap, &h->hcap, &h->hscap);
+  rc = geometry_for(h, n_replicas, &h->lcap, &h->hcap, &h->hscap, &h->stack_lds);
   if (rc != FCS_OK) return rc;
   h->spill_stride = static_cast<int64_t>(kSpillWordsPerSlot) * h->hcap + static_cast<int64_t>(S_NFIELDS) * h->hscap;
   hipError_t e = hipMemcpyAsync(ws, h->blob.data(), h->blob.size() * sizeof(uint32_t),
@@ -449,7 +463,7 @@ struct LaunchSite {
   unsigned long long* pace;
   uint32_t launch_seq;
   fcs_outputs out;
-  int32_t lcap, hcap, hscap;
+  int32_t lcap, hcap, hscap, stack_lds;
   int64_t spill_stride;
 };
 
@@ -467,7 +481,7 @@ static int run_on(fcs_engine* h, const LaunchSite& site, int64_t replica_base, i
   kp.n_steps = static_cast<int32_t>(n_steps);
   kp.seed_lo = static_cast<uint32_t>(seed);
   kp.seed_hi = static_cast<uint32_t>(seed >> 32);
-  kp.lcap = site.lcap; kp.hcap = site.hcap; kp.hscap = site.hscap;
+  kp.lcap = site.lcap; kp.hcap = site.hcap; kp.hscap = site.hscap; kp.stack_lds = site.stack_lds;
   kp.class_words = h->has_classes ? class_lds_words(h->n_classes) : 0;
   kp.wheel_slots = h->wheel_slots;
   kp.all_policies = (h->has_classes || h->has_alpha || h->has_budget_modes || h->has_mc || h->time_c0 != 0) ? 1 : 0;
@@ -503,6 +517,7 @@ static int run_on(fcs_engine* h, const LaunchSite& site, int64_t replica_base, i
   h->run_out = site.out;
   h->run_lcap = site.lcap;
   h->run_hcap = site.hcap;
+  h->run_stack_lds = site.stack_lds;
   return FCS_OK;
 }
 
@@ -518,7 +533,7 @@ int fcs_run_from(fcs_handle h, int64_t replica_base, int64_t n_replicas, int64_t
   site.pace = reinterpret_cast<unsigned long long*>(static_cast<char*>(h->workspace) + need - 256);
   site.launch_seq = ++h->launch_seq;
   site.out = h->out;
-  site.lcap = h->lcap; site.hcap = h->hcap; site.hscap = h->hscap;
+  site.lcap = h->lcap; site.hcap = h->hcap; site.hscap = h->hscap; site.stack_lds = h->stack_lds;
   site.spill_stride = h->spill_stride;
   return run_on(h, site, replica_base, n_replicas, n_steps, seed, stream);
 }
@@ -527,7 +542,7 @@ int fcs_run_static(fcs_handle h, const fcs_outputs* o, int64_t n_replicas, int64
                    void* stream) {
   if (!h || !o || !o->counters) return FCS_EINVAL;
   LaunchSite site{};
-  int rc = geometry_for(h, n_replicas, &site.lcap, &site.hcap, &site.hscap);
+  int rc = geometry_for(h, n_replicas, &site.lcap, &site.hcap, &site.hscap, &site.stack_lds);
   if (rc != FCS_OK) return rc;
   site.spill_stride = static_cast<int64_t>(kSpillWordsPerSlot) * site.hcap + static_cast<int64_t>(S_NFIELDS) * site.hscap;
   // the same layout as a caller's workspace, the pacing words apart at the end of the array
@@ -706,7 +721,7 @@ int fcs_geometry(fcs_handle h, int32_t* lds_slots, int32_t* lds_bytes, int32_t* 
   if (!h->bound && !h->ran) return FCS_ESTATE;
   const int32_t lc = h->ran ? h->run_lcap : h->lcap, hc = h->ran ? h->run_hcap : h->hcap;
   if (lds_slots) *lds_slots = lc;
-  if (lds_bytes) *lds_bytes = lds_words(lc, extra_lds_words(h)) * 4;
+  if (lds_bytes) *lds_bytes = lds_words(lc, h->ran ? h->run_stack_lds : h->stack_lds, extra_lds_words(h)) * 4;
   if (spill_slots) *spill_slots = hc;
   return FCS_OK;
 }

@@ -36,7 +36,10 @@ constexpr int S_NFIELDS = 4;
 constexpr int kWave = 64;
 constexpr int kGuideBits = 16;
 constexpr int kLdsBlock = 256;       // slots per b128 pass over the LDS tier
-constexpr int kStackLds = 64;        // evicted-stack entries kept in LDS
+// Evicted-stack entries kept in LDS: a launch parameter (KParams::stack_lds), chosen with the number of LDS
+// slots so that a path's LDS comes to a whole number of kilobytes, the unit in which a compute unit hands
+// its LDS out.
+constexpr int kStackLdsMin = 48, kStackLdsMax = 128;
 constexpr int kScratchWords = 64;
 constexpr int kCompactSlack = 64;    // compact when this many dead slots have accumulated
 constexpr int kLdsCompactMin = 16;   // ... or this many when the next slot would be the first outside LDS
@@ -54,6 +57,7 @@ struct KParams {
   int32_t n_steps;
   uint32_t seed_lo, seed_hi;
   int32_t lcap, hcap, hscap;  // LDS slots, spill slots, spill stack entries (per path)
+  int32_t stack_lds;          // entries of the evicted stack kept in LDS (kStackLdsMin .. kStackLdsMax)
   int32_t class_words;        // LDS words of the per-class tables (0 without CLASSES cells)
   int32_t wheel_slots;        // MC cells with known request types: future slots that the wheel of predicted
                               // departures spans (a multiple of 64, at least the longest output; else 0)
@@ -77,8 +81,8 @@ struct KParams {
 // CLASSES cells keep three tables of 64 words per class in LDS (arrival counts of the current window,
 // cumulative counts of the block the reader of each class queue stands in, arrival-law thresholds)
 inline int class_lds_words(int n_classes) { return 3 * kWave * n_classes; }
-inline int lds_words(int lcap, int class_words) {
-  return kLdsWordsPerSlot * lcap + S_NFIELDS * kStackLds + kScratchWords + class_words;
+inline int lds_words(int lcap, int stack_lds, int class_words) {
+  return kLdsWordsPerSlot * lcap + S_NFIELDS * stack_lds + kScratchWords + class_words;
 }
 
 // Cells of an engine that take part in the ordering of a launch (more than that: cells run in index order).

@@ -25,7 +25,7 @@
 //                function of (seed, replica, slot, index), so the FIFO of fresh requests is
 //                re-generated 64 arrivals at a time when they are admitted.  Evicted requests
 //                re-enter at the front of Q, newest eviction deepest: a stack (first
-//                kStackLds entries in LDS, the rest in the spill region).
+//                entries in LDS, the rest in the spill region).
 //   scalars      U, |P|, cursors and counts are wave-uniform and stay in scalar registers;
 //                statistics accumulate in lanes of a few vector registers.
 #include <hip/hip_runtime.h>
@@ -205,7 +205,7 @@ __global__ __launch_bounds__(1024) void fcs_order_kernel(uint32_t* sched, int n_
 }  // namespace
 
 int launch_sim(KParams kp, uint32_t sched_off, void* stream) {
-  const size_t lds = static_cast<size_t>(lds_words(kp.lcap, kp.class_words + 2 * kp.wheel_slots)) * sizeof(int32_t);
+  const size_t lds = static_cast<size_t>(lds_words(kp.lcap, kp.stack_lds, kp.class_words + 2 * kp.wheel_slots)) * sizeof(int32_t);
   void (*kernel)(const KParams) = kp.all_policies ? (kp.wheel_slots > 0 ? fcs_sim_mck_kernel : fcs_sim_all_kernel)
                                   : (kp.flags & FCS_FLAG_SKIP_IDLE) ? fcs_sim_skip_kernel : fcs_sim_kernel;
   if (lds > 48 * 1024) {
