@@ -140,7 +140,8 @@ typedef struct fcs_params {
                            * M / (min l + 1) + 1, and with CLASSES cells at least
                            * sum_k b_k (ceil(l_k / min(c, tau)) + o_k + 1); the default
                            * is at most 8192 */
-  int32_t lds_slots;      /* active-set slots kept in LDS per path; 0 = automatic  */
+  int32_t lds_slots;      /* active-set slots kept in LDS per path; 0 = automatic, else 256, 320, 384,
+                             448, 512 or a multiple of 256 up to 4096                               */
   /* Slots of variable duration (all three 0: every slot lasts one time unit).  Time runs
    * in the units of the arrival laws: n_u requests arrive in unit u; slot t starts at time
    * tau_t (tau_1 = 1), sees the arrivals of the units up to tau_t and lasts

@@ -54,8 +54,7 @@ struct fcs_engine {
 namespace {
 
 constexpr int32_t kLimit = 1 << 30;
-// an expected active set up to this size gets one block of 256 LDS slots (see geometry_for)
-constexpr double kSmallActive = 180.0;
+constexpr double kLdsFill = 0.85;  // share of a path's LDS slots that its expected active set may take
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -142,7 +141,8 @@ bool params_ok(const fcs_params* p) {
   if (p->hist_shift < 0 || p->hist_shift > 30 || p->max_requests < 0) return false;
   if (p->max_active < 0 || p->max_active > (1 << 24)) return false;
   if (p->lds_slots != 0 &&
-      (p->lds_slots < kLdsBlock || p->lds_slots > 4096 || p->lds_slots % kLdsBlock != 0))
+      (p->lds_slots < kLdsBlock || p->lds_slots > 4096 || p->lds_slots % kWave != 0 ||
+       (p->lds_slots > 2 * kLdsBlock && p->lds_slots % kLdsBlock != 0)))
     return false;
   return true;
 }
@@ -343,6 +343,12 @@ int fcs_create(const fcs_params* p, fcs_handle* out) {
     std::memcpy(h->blob.data() + h->cells_off + 4 * i, &d, sizeof(d));
   }
   for (int32_t c = 0; c + 1 < p->n_classes; ++c) h->blob[h->class_off + c] = p->class_thr[c];
+  // only the kernel of the FLOW and GREEDY cells takes LDS slots that are not a multiple of 256
+  if (p->lds_slots % kLdsBlock != 0 &&
+      (h->has_classes || h->has_alpha || h->has_budget_modes || h->has_mc || h->time_c0 != 0)) {
+    delete h;
+    return FCS_EINVAL;
+  }
   for (int32_t i = 0; i < p->n_cells; ++i)
     if (p->cells[i].policy == FCS_POLICY_FLOW || p->cells[i].policy == FCS_POLICY_GREEDY)
       h->expected_active = std::max(h->expected_active, expected_active_of(p, p->cells[i]));
@@ -378,13 +384,17 @@ static int geometry_for(fcs_engine* h, int64_t n_replicas, int32_t* lcap, int32_
   max_active = static_cast<int64_t>(round_up(static_cast<size_t>(max_active), kWave));
   int32_t lc = h->lds_slots_param;
   const bool plain = !(h->has_classes || h->has_alpha || h->has_budget_modes || h->has_mc || h->time_c0 != 0);
-  if (lc == 0 && plain && n_paths > 2048 && h->expected_active <= kSmallActive) {
+  if (lc == 0 && plain && n_paths > 2048) {
     // The kernel of the FLOW and GREEDY cells runs four wavefronts per SIMD, and a path is a chain of
     // dependent instructions: with more paths than the chip holds at two per SIMD, throughput is set by how
-    // many are resident.  One block of 256 slots (8.25 KB with the stack) lets 16 of them share a compute
-    // unit; it is taken when the expected active set leaves room for its fluctuations and for the dead
-    // slots between compactions.  A path whose active set outgrows it goes on in the spill region.
-    lc = kLdsBlock;
+    // many are resident.  320 slots (with a stack of 64 entries, eight 1,280-byte granules of LDS) let 16
+    // paths share a compute unit, 384 twelve, 448 eleven, 512 ten.  The fewest slots are taken that leave
+    // the expected active set some 15 % of them for its fluctuations and for the dead slots between
+    // compactions (measured on a heavy-tailed workload at several memory sizes: 320 slots beat 384 up to a
+    // mean active set of about 275, 384 beat 512 beyond 290).  A path whose active set outgrows its slots
+    // goes on in the spill region.
+    const int64_t want = static_cast<int64_t>(round_up(static_cast<size_t>(std::ceil(h->expected_active / kLdsFill)), kWave));
+    if (want <= 2 * kLdsBlock) lc = static_cast<int32_t>(std::max<int64_t>(want, kLdsBlock + kWave));
   }
   if (lc == 0) {
     // spread the paths over the 256 compute units and give each wavefront an equal share of
@@ -397,6 +407,8 @@ static int geometry_for(fcs_engine* h, int64_t n_replicas, int32_t* lcap, int32_
     lc = static_cast<int32_t>(words / kLdsWordsPerSlot / kLdsBlock * kLdsBlock);
     lc = std::min(std::max(lc, kLdsBlock), 2048);
   }
+  // only the kernels of the FLOW and GREEDY cells take LDS slots that are not a multiple of 256
+  if (!plain && lc % kLdsBlock != 0) return FCS_EINVAL;
   lc = static_cast<int32_t>(std::min<int64_t>(lc, static_cast<int64_t>(round_up(max_active, kLdsBlock))));
   *lcap = lc;
   *hcap = static_cast<int32_t>(std::max<int64_t>(max_active - lc, 0));

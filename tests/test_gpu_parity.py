@@ -117,6 +117,34 @@ def test_token_budget_about_the_size_of_the_active_set():
     assert got["stalled"].min() > 50 * wl.n_steps and got["max_p"].min() > 400
 
 
+def test_lds_slots_between_one_and_two_blocks():
+    # 320, 384 and 448 LDS slots: the second block of 256 is only partly there.  Active sets that stay inside
+    # it, cross its end into the spill region and back, stall under a binding token budget and are evicted
+    stall = configs.toy(capacity=20000, token_budget=320, prefill_chunk=100, lam=6.0, b=7.0, o_mean=55.0, o_cap=240,
+                        l_range=(4, 40), n_replicas=4, n_steps=1500, max_requests=0)
+    evict = configs.toy(capacity=16000, token_budget=400, prefill_chunk=64, lam=7.0, b=8.0, o_mean=50.0, o_cap=240,
+                        l_range=(4, 40), n_replicas=4, n_steps=1500, max_requests=0)
+    heavy = configs.config2(oracle.stability_bound).scaled(n_replicas=3, n_steps=12000)
+    for lc in (320, 384, 448):
+        for wl, ids in ((stall, None), (evict, None), (_big_active(n_replicas=3, n_steps=2000), None), (heavy, [0, 2])):
+            eng = run(wl, lds_slots=lc, max_active=2048)
+            assert eng.geometry()["lds_slots"] == lc
+            got, _, _ = compare(eng, wl, replica_ids=ids, label=f"{wl.name}, {lc} LDS slots")
+            ref, _ = run(wl, lds_slots=512, max_active=2048).stats()
+            for k in got:
+                assert np.array_equal(got[k], ref[k]), (lc, wl.name, k)
+        # and through the compiler's rendition of the slot
+        eng = run(stall, lds_slots=lc, max_active=2048, general_code=True)
+        compare(eng, stall, label=f"general code, {lc} LDS slots")
+    got, _ = run(stall, lds_slots=320, max_active=2048).stats()
+    assert got["stalled"].min() > 50 * stall.n_steps and got["max_p"].min() > 400       # past 320 and 384 slots
+    got, _ = run(evict, lds_slots=320, max_active=2048).stats()
+    assert got["evictions"].min() > 1000 and got["max_p"].min() > 300
+    # the other kernels take their LDS slots in blocks of 256
+    with pytest.raises(fcs.FcsError):
+        fcs.Engine(configs.alpha_sweep(n_replicas=2, n_steps=10), lds_slots=320)
+
+
 def test_edge_cases_of_the_other_policies():
     obs = dict(trace_every=7, hist_bins=64, max_requests=256)
     kc = lambda **kw: configs.known_classes(n_replicas=3, **obs, **kw)
@@ -215,7 +243,7 @@ def test_config3_full_size_sampled_paths():
     from concurrent.futures import ThreadPoolExecutor
     wl = configs.config3(oracle.stability_bound)
     eng = run(wl)
-    assert eng.n_paths == 262144 and eng.n_steps == 50000 and eng.geometry()["lds_slots"] == 256
+    assert eng.n_paths == 262144 and eng.n_steps == 50000 and eng.geometry()["lds_slots"] == 320
     got, _ = eng.stats()
     assert not np.any(got["error"])
     R = eng.n_replicas

@@ -76,6 +76,13 @@ def test_create_validates_parameters():
     assert _create(ok.scaled(prefill_chunk=0)) == -1
     assert _create(ok.scaled(capacity=100)) == -1            # max l + max o = 140 > M
     assert _create(ok, lds_slots=100) == -1
+    # LDS slots per path: 256 to 512 in steps of 64, then in steps of 256; the kernels of the other policies
+    # and of slots of variable duration take steps of 256 only
+    for slots, rc in ((256, 0), (320, 0), (448, 0), (512, 0), (576, -1), (768, 0), (4096, 0), (4352, -1), (192, -1)):
+        assert _create(ok, lds_slots=slots) == rc, slots
+    assert _create(configs.alpha_sweep(n_replicas=2, n_steps=10), lds_slots=320) == -1
+    assert _create(configs.alpha_sweep(n_replicas=2, n_steps=10), lds_slots=512) == 0
+    assert _create(ok.scaled(time_model=(2, 1, 1)), lds_slots=384) == -1
     bad = laws.Law.__new__(laws.Law)
     object.__setattr__(bad, "lo", 1)
     object.__setattr__(bad, "thr", np.array([5, 3], np.uint32))
