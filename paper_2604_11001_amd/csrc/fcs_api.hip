@@ -225,10 +225,13 @@ double law_mean_chunks(const fcs_law& L, int64_t c) {
 // (activation rate) x E[S], the rate being at most the arrival rate and, under Algorithm 2, the mean
 // budget b.  The memory caps it: over its stay a request holds l per prefill slot and l + j in the
 // slot of token j, E[w] + E[l (ceil(l / c) - 1)] in all, so no more than M E[S] / that fit on average.
+// Where the requests activated per slot want more than four fifths of the token budget (l prompt tokens
+// and o output tokens each), prompts wait for budget inside the active set and evicted requests prefill
+// again: the set then grows until the memory stops it, and the memory figure alone is the estimate.
 double expected_active_of(const fcs_params* p, const fcs_cell& c) {
   const double two32 = 4294967296.0;
   const int64_t chunk = std::max<int64_t>(1, std::min<int64_t>(p->prefill_chunk, p->token_budget));
-  double es = 0.0, hold = 0.0, prev = 0.0;
+  double es = 0.0, hold = 0.0, prev = 0.0, tokens = 0.0;
   for (int32_t k = 0; k < p->n_classes; ++k) {
     const double cur = (k + 1 < p->n_classes) ? static_cast<double>(p->class_thr[k]) : two32;
     const double pk = (cur - prev) / two32;
@@ -238,6 +241,7 @@ double expected_active_of(const fcs_params* p, const fcs_cell& c) {
     law_moments(p->decode[k], eo, eo2);
     const double ech = law_mean_chunks(p->prompt[k], chunk);
     es += pk * (ech + eo - 1.0);
+    tokens += pk * (el + eo);
     // l and o independent; E[l (ceil(l / c) - 1)] taken as E[l] E[ceil(l / c) - 1], good enough for a size
     hold += pk * (el * eo + 0.5 * (eo + eo2) + el * (ech - 1.0));
   }
@@ -248,6 +252,7 @@ double expected_active_of(const fcs_params* p, const fcs_cell& c) {
     rate = std::min(rate, static_cast<double>(c.b_floor) + static_cast<double>(c.b_frac_thr) / two32);
   const double by_rate = rate * es;
   const double by_memory = hold > 0.0 ? static_cast<double>(p->capacity) * es / hold : by_rate;
+  if (rate * tokens > 0.8 * static_cast<double>(p->token_budget)) return by_memory;
   return std::min(by_rate, by_memory);
 }
 

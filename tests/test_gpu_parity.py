@@ -145,6 +145,17 @@ def test_lds_slots_between_one_and_two_blocks():
         fcs.Engine(configs.alpha_sweep(n_replicas=2, n_steps=10), lds_slots=320)
 
 
+def test_lds_slots_follow_the_expected_active_set():
+    # many paths of FLOW cells: the fewest LDS slots of which the expected active set fills at most 85 %
+    base = configs.config2(oracle.stability_bound).scaled(n_replicas=700, n_steps=64)     # 2,100 paths
+    for scale, slots in ((0.5, 320), (1.0, 320), (1.45, 384), (1.8, 448), (2.3, 512)):
+        wl = base.scaled(capacity=int(base.capacity * scale))
+        eng = fcs.Engine(wl)
+        assert eng.geometry()["lds_slots"] == slots, (scale, eng.geometry())
+    # few paths: every one is resident anyway, so each gets as much LDS as the compute units have to give
+    assert fcs.Engine(base.scaled(n_replicas=8)).geometry()["lds_slots"] >= 512
+
+
 def test_edge_cases_of_the_other_policies():
     obs = dict(trace_every=7, hist_bins=64, max_requests=256)
     kc = lambda **kw: configs.known_classes(n_replicas=3, **obs, **kw)
