@@ -672,6 +672,41 @@ def _plain_random_workload(rng, k):
                     max_requests=4096)
 
 
+def _plain_random_big_workload(rng, k):
+    """FLOW and GREEDY cells with active sets of 150 to 700 requests: around the LDS slots a path may have."""
+    l_hi = int(rng.integers(4, 40))
+    prompt = laws.uniform_int(int(rng.integers(1, l_hi)), l_hi)
+    o_cap = int(rng.integers(40, 200))
+    o_mean = float(rng.uniform(15.0, 60.0))
+    decode = laws.geometric(o_mean, cap=o_cap)
+    active = int(rng.integers(150, 700))
+    M = int(active * (0.5 * (prompt.lo + l_hi) + 0.5 * o_mean))
+    lam = min(float(active / o_mean * rng.uniform(0.7, 1.3)), 16.0)   # (a count law has at most 63 thresholds)
+    tau = INF if rng.random() < 0.3 else int(active * rng.uniform(0.6, 1.6))
+    chunk = INF if rng.random() < 0.3 else int(rng.integers(2, 48))
+    cells = (flow_cell(0, lam * float(rng.uniform(0.9, 1.3))), greedy_cell(0))
+    return Workload(name=f"plain-big-{k}", capacity=max(M, l_hi + o_cap), token_budget=tau, prefill_chunk=chunk,
+                    mixture=laws.single(prompt, decode), arrival_laws=(laws.poisson_counts(lam),), cells=cells,
+                    n_replicas=2, n_steps=int(rng.integers(200, 700)), seed=5000 + k,
+                    trace_every=int(rng.choice([0, 10, 64])), hist_bins=64, hist_shift=int(rng.integers(0, 3)),
+                    max_requests=1 << 14)
+
+
+def test_random_workloads_around_the_lds_slots():
+    rng = np.random.default_rng(20261130)
+    seen = set()
+    for k in range(36):
+        w = _plain_random_big_workload(rng, k)
+        lc = int(rng.choice([256, 320, 384, 448, 512]))
+        kw = dict(lds_slots=lc, max_active=4096, skip_idle=bool(k % 3 == 0))
+        got, _, _ = compare(run(w, **kw), w, label=f"{w.name} M={w.capacity} tau={w.token_budget} c={w.prefill_chunk} "
+                                                   f"T={w.n_steps} lds={lc}")
+        seen.add((lc, bool(got["max_p"].max() > lc), bool(got["max_p"].max() > 256)))
+    # every size above one block met active sets inside its slots and past them (the spill region)
+    for lc in (320, 384, 448, 512):
+        assert any(s[0] == lc and s[1] for s in seen) and any(s[0] == lc and not s[1] for s in seen), (lc, sorted(seen))
+
+
 def test_event_skipping_changes_no_output():
     # configuration 0: seven slots in eight have no arrival, admission, prefill or completion
     wl = configs.config0(oracle.stability_bound)
