@@ -621,6 +621,8 @@ def test_random_small_workloads():
         rng = np.random.default_rng(seed)
         for k in range(count):
             wl, kw = _random_workload(rng, k)
+            if seed != 20260411 and wl.capacity > 6000:   # the oracle's MC check is quadratic in the active set
+                wl = wl.scaled(cells=tuple(c for c in wl.cells if c.policy != configs.MC))
             eng = run(wl, **kw)
             done += 1
             try:
@@ -634,6 +636,8 @@ def test_random_small_workloads():
                 outgrown += 1
                 continue
             check_summary(eng, wl, got)
+        if len(runs) > 1:   # a campaign by hand: a line per generator seed (run with -s) shows that it moves
+            print(f"generator seed {seed}: {count} workloads compared, {done} so far", flush=True)
     assert outgrown <= done // 100, (outgrown, done)
 
 
