@@ -709,6 +709,21 @@ def test_random_workloads_around_the_lds_slots():
     # every size above one block met active sets inside its slots and past them (the spill region)
     for lc in (320, 384, 448, 512):
         assert any(s[0] == lc and s[1] for s in seen) and any(s[0] == lc and not s[1] for s in seen), (lc, sorted(seen))
+    # FCS_PARITY_SEEDS="a:b" adds 20 workloads for each generator seed in [a, b) (a longer campaign by hand)
+    import os
+    if os.environ.get("FCS_PARITY_SEEDS"):
+        a, b = (int(v) for v in os.environ["FCS_PARITY_SEEDS"].split(":"))
+        done = 0
+        for seed in range(a, b):
+            rng = np.random.default_rng(seed)
+            for k in range(20):
+                w = _plain_random_big_workload(rng, k)
+                kw = dict(lds_slots=int(rng.choice([256, 320, 384, 448, 512, 768])), max_active=4096,
+                          skip_idle=bool(rng.random() < 0.3), general_code=bool(rng.random() < 0.1))
+                compare(run(w, **kw), w, label=f"seed {seed}/{k}: {w.name} M={w.capacity} tau={w.token_budget} "
+                                               f"c={w.prefill_chunk} T={w.n_steps} {kw}")
+                done += 1
+            print(f"generator seed {seed}: {done} workloads compared so far", flush=True)
 
 
 def test_event_skipping_changes_no_output():
