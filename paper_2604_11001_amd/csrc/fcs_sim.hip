@@ -19,7 +19,10 @@
 //                         whose budget binds moves the entries of the stalled requests by one.
 //                  FOOT   l + o, what the request releases when it completes (LDS only, next
 //                         to END: the two are read together)
-//                  PLEFT  prompt tokens still to prefill; meaningful while END is -1 (0 = unused)
+//                  PLEFT  prompt tokens still to prefill; meaningful while END is -1 (0 = unused).  Once the
+//                         request decodes the word means nothing to anybody but the slot loop, whose
+//                         general prefill pass leaves -t there when the prompt ended in slot t (the
+//                         stall pass of that slot reads it)
 //                  REC    {l, o, arrival slot, id}
 //   waiting queue  requests that were never activated are not stored: arrivals are a pure
 //                function of (seed, replica, slot, index), so the FIFO of fresh requests is
