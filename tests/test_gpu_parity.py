@@ -726,6 +726,23 @@ def test_random_workloads_around_the_lds_slots():
             print(f"generator seed {seed}: {done} workloads compared so far", flush=True)
 
 
+def test_outputs_of_one_or_two_tokens_with_many_prompts_in_flight():
+    # a prompt that ends yields token 1 in the same slot, so with o = 1 the request completes there and then:
+    # many such prompts per slot (the prefill pass over chunks of slots), with and without a binding budget
+    n = 0
+    for o_law in (laws.point(1), laws.uniform_int(1, 2), laws.geometric(1.5, cap=70)):
+        for tau, chunk in ((INF, INF), (64, 8), (40, 3), (25, INF)):
+            for (lam, M), lc in (((6.0, 3000), 256), ((12.0, 9000), 320), ((3.0, 800), 512)):
+                wl = Workload(name="short-outputs", capacity=M, token_budget=tau, prefill_chunk=chunk,
+                              mixture=laws.single(laws.uniform_int(2, 30), o_law),
+                              arrival_laws=(laws.poisson_counts(lam),),
+                              cells=(flow_cell(0, lam * 1.1), greedy_cell(0), flow_cell(0, 2.5)), n_replicas=2,
+                              n_steps=300, seed=77 + n, trace_every=0, hist_bins=32, max_requests=1 << 13)
+                compare(run(wl, lds_slots=lc, max_active=4096), wl,
+                        label=f"{o_law.name} tau={tau} c={chunk} lam={lam} M={M} lds={lc}")
+                n += 1
+
+
 def test_event_skipping_changes_no_output():
     # configuration 0: seven slots in eight have no arrival, admission, prefill or completion
     wl = configs.config0(oracle.stability_bound)
