@@ -190,14 +190,22 @@ enum { SL_SUM_U = 0, SL_SUM_P, SL_SUM_Q, SL_DEC_TOK, SL_ACT, SL_DONE, SL_EVICT, 
 // a few slow paths rather than the mean of a cell: workgroups are handed out in index order, so the cells
 // that hold them should start first.
 __global__ __launch_bounds__(1024) void fcs_order_kernel(uint32_t* sched, int n_cells, uint32_t seq) {
+  // the times as 32-bit keys in LDS (saturated: an order is all that is wanted), so that the n^2 comparisons
+  // read LDS words that all threads ask for at once instead of device memory
+  __shared__ uint32_t key[kMaxOrderedCells];
   unsigned long long* const cost_prev = reinterpret_cast<unsigned long long*>(sched) + ((seq & 1u) ^ 1u) * n_cells;
   unsigned long long* const cost_cur = reinterpret_cast<unsigned long long*>(sched) + (seq & 1u) * n_cells;
   int32_t* const order = reinterpret_cast<int32_t*>(sched + 4u * n_cells);
   for (int i = static_cast<int>(threadIdx.x); i < n_cells; i += static_cast<int>(blockDim.x)) {
-    const unsigned long long mine = cost_prev[i];
+    const unsigned long long c = cost_prev[i];
+    key[i] = c > 0xffffffffull ? 0xffffffffu : static_cast<uint32_t>(c);
+  }
+  __syncthreads();
+  for (int i = static_cast<int>(threadIdx.x); i < n_cells; i += static_cast<int>(blockDim.x)) {
+    const uint32_t mine = key[i];
     int rank = 0;
     for (int j = 0; j < n_cells; ++j) {
-      const unsigned long long other = cost_prev[j];
+      const uint32_t other = key[j];
       rank += (other > mine || (other == mine && j < i)) ? 1 : 0;
     }
     order[rank] = i;

@@ -743,6 +743,26 @@ def test_outputs_of_one_or_two_tokens_with_many_prompts_in_flight():
                 n += 1
 
 
+def test_grid_of_8192_cells_every_cell_runs_once():
+    # the largest number of cells whose launch order follows the times of the launch before: whatever the
+    # order, every path runs exactly once (second launch: ordered by what the first one measured)
+    wl = configs.config3(oracle.stability_bound, n_lambda=128, n_b=64).scaled(n_replicas=1, n_steps=150, hist_bins=0)
+    assert len(wl.cells) == 8192
+    eng = run(wl)
+    first, _ = eng.stats()
+    eng.run()
+    got, _ = eng.stats()
+    for k in first:
+        assert np.array_equal(first[k], got[k]), k
+    for ci in range(0, 8192, 97):
+        ref = oracle.run_cell(wl, ci)
+        for k in ("arrived", "completed", "sum_u", "sum_p", "sum_q", "final_u", "digest"):
+            assert int(got[k][ci]) == int(ref["counters"][k][0]), (ci, k)
+    # cells of one arrival stream share their arrivals: 64 rows each of 128 streams
+    arrived = got["arrived"].reshape(128, 64)
+    assert np.all(arrived == arrived[:, :1]) and len(set(arrived[:, 0].tolist())) >= 30
+
+
 def test_event_skipping_changes_no_output():
     # configuration 0: seven slots in eight have no arrival, admission, prefill or completion
     wl = configs.config0(oracle.stability_bound)
